@@ -1,0 +1,251 @@
+"""Pins for the oracle's quantise / pack / unpack / de-quantise (Sec. 2.3 Eq. 4-5, Theorem 1, App. A.1).
+
+Each test checks the oracle against something other than itself: hand-derived closed forms, invariants the
+paper states, numpy's own bit packing, float64 re-derivations from the published (Z, S).
+"""
+import os
+
+import numpy as np
+import pytest
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+WIDTHS = (2, 4, 8)
+
+
+def _single_width(oracle, rows, b, seed=0, want_codes=True):
+    """Quantise every row of `rows` (2-D fp32) at width b; one peer, identity send list."""
+    rows = np.ascontiguousarray(rows, dtype=np.float32)
+    n, dim = rows.shape
+    bits = np.full(n, b, dtype=np.uint8)
+    perm, off, pbp = oracle.plan_layout(dim, bits, np.zeros(n, dtype=np.int32), 1)
+    assert np.array_equal(perm, np.arange(n))
+    packed, params, codes = oracle.quantize_pack(rows, dim, np.arange(n, dtype=np.int32), bits, off, seed,
+                                                 int(pbp[-1]), want_codes=want_codes)
+    return packed, params, codes, off
+
+
+def test_closed_form_rows_and_bytes(oracle):
+    pats = {}
+    for line in open(os.path.join(GOLDEN, "pack_patterns.txt")):
+        if line.strip() and not line.startswith("#"):
+            b, hexbytes = line.split()
+            pats[int(b)] = bytes.fromhex(hexbytes)
+    for b in WIDTHS:
+        L = (1 << b) - 1
+        row = np.arange(L + 1, dtype=np.float32)[None, :]
+        for seed in (0, 1, 7, 2**40 + 3, 2**64 - 1):
+            packed, params, codes, _ = _single_width(oracle, row, b, seed)
+            assert params[0, 0] == 0.0 and params[0, 1] == 1.0
+            assert np.array_equal(codes[0], np.arange(L + 1))
+            if b in pats:
+                assert packed.tobytes() == pats[b]
+            else:
+                assert packed.tobytes() == bytes(range(256))
+            out = np.full((1, L + 1), np.nan, dtype=np.float32)
+            oracle.unpack_dequant(packed, params, np.array([b], np.uint8), np.array([0], np.int64),
+                                  np.array([0], np.int32), L + 1, out)
+            assert np.array_equal(out, row)
+
+
+def test_affine_closed_form(oracle):
+    # the code grid is invariant under h -> a*h + c for power-of-two a and exactly representable c
+    for b in WIDTHS:
+        L = (1 << b) - 1
+        row = (np.arange(L + 1, dtype=np.float32) * np.float32(0.25) - np.float32(3.0))[None, :]
+        packed, params, codes, _ = _single_width(oracle, row, b, seed=5)
+        assert params[0, 0] == np.float32(-3.0) and params[0, 1] == np.float32(0.25)
+        assert np.array_equal(codes[0], np.arange(L + 1))
+
+
+def test_code_range_and_endpoints(oracle):
+    rng = np.random.default_rng(11)
+    for b in WIDTHS:
+        L = (1 << b) - 1
+        rows = rng.standard_normal((64, 97), dtype=np.float32) * rng.choice([1e-6, 1.0, 3e4], size=(64, 1)).astype(np.float32)
+        rows[5] = np.float32(2.5)                              # constant row
+        rows[6, :] = 0.0
+        rows[6, 3] = -0.0                                      # both zeros
+        rows[7] = np.abs(rows[7])                              # non-negative
+        rows[8, :50] = 0.0
+        for seed in range(20):
+            _, params, codes, _ = _single_width(oracle, rows, b, seed)
+            assert codes.max() <= L
+            amin, amax = rows.argmin(1), rows.argmax(1)
+            r = np.arange(rows.shape[0])
+            const = rows.max(1) == rows.min(1)
+            assert np.all(codes[r, amin] == 0)
+            assert np.all(codes[r, amax][~const] == L)
+            assert np.all(codes[const] == 0)
+            assert np.all(params[const, 1] == 0)
+            assert np.array_equal(params[:, 0], rows.min(1) + np.float32(0.0))
+            assert not np.signbit(params[6, 0])
+
+
+def test_overshoot_of_top_element_is_clamped(oracle):
+    # search for rows where (max - Z) * inv rounds above 2^b - 1 in fp32: the clamp must still give code L
+    rng = np.random.default_rng(3)
+    found = 0
+    for b in WIDTHS:
+        L = np.float32((1 << b) - 1)
+        lo = rng.standard_normal(20000).astype(np.float32)
+        hi = lo + np.abs(rng.standard_normal(20000).astype(np.float32)) + np.float32(1e-3)
+        rng32 = (hi + np.float32(0)) - (lo + np.float32(0))
+        inv = L / rng32
+        over = (hi - lo) * inv > L
+        found += int(over.sum())
+        idx = np.nonzero(over)[0][:50]
+        if idx.size == 0:
+            continue
+        rows = np.stack([lo[idx], hi[idx], (lo[idx] + hi[idx]) / 2], axis=1).astype(np.float32)
+        _, _, codes, _ = _single_width(oracle, rows, int(np.log2(L + 1)), seed=1)
+        assert np.all(codes[:, 1] == int(L)) and np.all(codes[:, 0] == 0)
+    assert found > 0, "the search should exercise the clamp at least once"
+
+
+def test_two_point_support_and_error_bound(oracle):
+    rng = np.random.default_rng(21)
+    rows = rng.standard_normal((40, 301), dtype=np.float32)
+    rows[::3] = np.maximum(rows[::3], 0)
+    for b in WIDTHS:
+        for seed in (0, 99):
+            packed, params, codes, off = _single_width(oracle, rows, b, seed)
+            Z = params[:, :1].astype(np.float64)
+            S = params[:, 1:].astype(np.float64)
+            x = (rows.astype(np.float64) - Z) / S                       # Eq. 4 argument in float64
+            lo, hi = np.floor(x - 1e-4), np.ceil(x + 1e-4)
+            assert np.all(codes >= lo) and np.all(codes <= hi)
+            assert np.all(np.abs(codes - x) < 1.0 + 1e-4)
+            out = np.zeros_like(rows)
+            oracle.unpack_dequant(packed, params, np.full(40, b, np.uint8), off, np.arange(40, dtype=np.int32),
+                                  301, out)
+            assert np.all(np.abs(out.astype(np.float64) - rows) <= S * (1 + 1e-4))
+            # Eq. 5 in float64 from the same codes; two fp32 roundings, each relative to its own operand size
+            assert np.all(np.abs(out - (codes * S + Z)) <= 1.3e-7 * (np.abs(codes * S) + np.abs(Z)))
+
+
+def _moments_over_seeds(oracle, rows, b, n_seeds):
+    rows = np.ascontiguousarray(rows, dtype=np.float32)
+    n, dim = rows.shape
+    bits = np.full(n, b, dtype=np.uint8)
+    _, off, pbp = oracle.plan_layout(dim, bits, np.zeros(n, dtype=np.int32), 1)
+    idx = np.arange(n, dtype=np.int32)
+    s1 = np.zeros((n, dim))
+    s2 = np.zeros((n, dim))
+    out = np.zeros_like(rows)
+    params = None
+    for seed in range(n_seeds):
+        packed, params, _ = oracle.quantize_pack(rows, dim, idx, bits, off, seed, int(pbp[-1]))
+        oracle.unpack_dequant(packed, params, bits, off, idx, dim, out)
+        o = out.astype(np.float64)
+        s1 += o
+        s2 += o * o
+    mean = s1 / n_seeds
+    var = s2 / n_seeds - mean * mean
+    return mean, var, params
+
+
+@pytest.mark.parametrize("b", WIDTHS)
+def test_unbiased_and_variance_bounded_over_1e5_seeds(oracle, b):
+    """Theorem 1: E[h^] = h.  Per element the rounding is a Bernoulli(f) step of size S, so the standard
+    error of the mean over N seeds is S*sqrt(f(1-f)/N) and Var <= S^2/4.  The 16-bit rounding probability
+    (reading R2) adds a bias of at most 2^-16 * S."""
+    N = 100_000
+    rng = np.random.default_rng(100 + b)
+    rows = rng.standard_normal((3, 64), dtype=np.float32)
+    rows[1] = np.maximum(rows[1], 0)
+    rows[2] *= np.float32(1e-3)
+    mean, var, params = _moments_over_seeds(oracle, rows, b, N)
+    Z = params[:, :1].astype(np.float64)
+    S = params[:, 1:].astype(np.float64)
+    x = (rows.astype(np.float64) - Z) / S
+    f = x - np.floor(x)
+    sigma = S * np.sqrt(f * (1 - f) / N)
+    slack = S * 2.0 ** -16 + 4 * np.spacing(np.abs(rows).astype(np.float32)).astype(np.float64)
+    err = np.abs(mean - rows)
+    assert np.all(err <= 5 * sigma + slack)
+    assert np.mean(err > 3 * sigma + slack) <= 0.02
+    assert np.all(var <= S * S / 4 * 1.02 + 1e-30)
+    # the Bernoulli variance itself: S^2 f (1 - f), to a few per cent where it is not tiny
+    expect = S * S * f * (1 - f)
+    big = f * (1 - f) > 0.05
+    assert np.allclose(var[big], expect[big], rtol=0.05)
+
+
+def test_variance_attains_quarter_bound(oracle):
+    # row [0, 0.5, 3] at 2 bits: S = 1, the middle element has fraction 1/2, variance S^2/4
+    rows = np.array([[0.0, 0.5, 3.0]], dtype=np.float32)
+    mean, var, params = _moments_over_seeds(oracle, rows, 2, 40_000)
+    assert params[0, 1] == 1.0
+    assert abs(var[0, 1] - 0.25) < 0.005
+    assert abs(mean[0, 1] - 0.5) < 0.01
+    assert var[0, 0] == 0 and var[0, 2] == 0
+
+
+@pytest.mark.parametrize("b", WIDTHS)
+def test_theorem1_variance_value(oracle, b):
+    """Theorem 1: with fractions spread uniformly the variance summed over the row is D * S^2 / 6."""
+    D = 4096
+    L = (1 << b) - 1
+    rng = np.random.default_rng(7 + b)
+    row = rng.uniform(0, L, size=D).astype(np.float32)
+    row[0], row[1] = 0.0, float(L)                       # pins Z = 0, S = 1
+    _, var, params = _moments_over_seeds(oracle, row[None, :], b, 3000)
+    S = float(params[0, 1])
+    assert S == 1.0
+    assert abs(var.sum() / (D * S * S / 6) - 1) < 0.03
+
+
+def test_pack_matches_numpy_bit_packing_and_round_trips(oracle):
+    rng = np.random.default_rng(5)
+    dims = list(range(1, 71)) + [128, 300, 602]
+    for b in WIDTHS:
+        for dim in dims:
+            rows = rng.standard_normal((3, dim), dtype=np.float32)
+            packed, params, codes, off = _single_width(oracle, rows, b, seed=dim)
+            stride = oracle.row_stride(dim, b)
+            assert stride == 4 * -(-dim * b // 32)
+            assert packed.shape[0] == 3 * stride
+            for r in range(3):
+                # little-endian bit string built by numpy, independent of the oracle's shifting
+                bitmat = ((codes[r][:, None] >> np.arange(b)) & 1).astype(np.uint8).reshape(-1)
+                expect = np.packbits(bitmat, bitorder="little")
+                got = packed[off[r]: off[r] + stride]
+                assert np.array_equal(got[: expect.shape[0]], expect)
+                assert np.all(got[expect.shape[0]:] == 0)                       # zero padding
+            out = np.zeros_like(rows)
+            back = oracle.unpack_dequant(packed, params, np.full(3, b, np.uint8), off,
+                                         np.arange(3, dtype=np.int32), dim, out, want_codes=True)
+            assert np.array_equal(back, codes)
+
+
+def test_dequant_scatters_only_listed_rows_and_columns(oracle):
+    rng = np.random.default_rng(9)
+    dim, ld = 10, 13
+    rows = rng.standard_normal((4, dim), dtype=np.float32)
+    packed, params, codes, off = _single_width(oracle, rows, 4, seed=2)
+    feat = np.full((9, ld), np.float32(-77.0))
+    halo = np.array([7, 2, 8, 0], dtype=np.int32)
+    oracle.unpack_dequant(packed, params, np.full(4, 4, np.uint8), off, halo, dim, feat)
+    untouched = np.ones((9, ld), dtype=bool)
+    untouched[halo, :dim] = False
+    assert np.all(feat[untouched] == -77.0)
+    for t, r in enumerate(halo):
+        expect = codes[t].astype(np.float32) * params[t, 1] + params[t, 0]   # numpy fp32: product, then sum
+        assert np.array_equal(feat[r, :dim], expect)
+
+
+def test_gather_uses_send_idx_and_ld(oracle):
+    rng = np.random.default_rng(10)
+    dim, ld = 9, 12
+    feat = rng.standard_normal((20, ld), dtype=np.float32)
+    send = np.array([4, 19, 4, 0], dtype=np.int32)               # a node may be sent twice
+    bits = np.array([2, 2, 8, 8], dtype=np.uint8)
+    off = np.array([0, 4, 8, 20], dtype=np.int64)
+    packed, params, codes = oracle.quantize_pack(feat, dim, send, bits, off, 3, 32, want_codes=True)
+    for s, r in enumerate(send):
+        assert params[s, 0] == feat[r, :dim].min()
+        L = (1 << int(bits[s])) - 1
+        assert codes[s, feat[r, :dim].argmax()] == L
+    # slots 0 and 2 carry the same node but are different messages: independent randomness is allowed,
+    # identical parameters up to the width are required
+    assert params[0, 0] == params[2, 0]
