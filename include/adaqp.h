@@ -1,0 +1,207 @@
+/*
+ * adaqp.h - C ABI of the quantised message path of one graph partition (AdaQP, arXiv 2306.01381) for
+ * AMD MI355X (gfx950).
+ *
+ * The library implements, for ONE device's partition, the data-parallel part of a GNN layer's aggregation
+ * step under message quantisation (Sec. 3.1 "Overview", Fig. 4):
+ *
+ *   send side     gather the marginal-node rows to send, per-row min / max, stochastic rounding to the
+ *                 assigned width b in {2, 4, 8}, sub-byte merging into per-peer byte buffers   (Sec. 2.3 Eq. 4,
+ *                 App. A.1, Sec. 5 "Implementation")
+ *   receive side  unpack the received buffers and de-quantise them into the halo rows          (Sec. 2.3 Eq. 5)
+ *   aggregation   out_v = sum over u in {v} U N(v) of alpha(u,v) * h_u as a CSR SpMM, central rows on a
+ *                 second stream so that they overlap the message path      (Sec. 2.1 Eq. 3, Sec. 3.4 Fig. 7)
+ *
+ * Conventions
+ *   - "dev" pointers are device pointers valid on the current HIP device, "host" pointers are host memory.
+ *   - Every buffer is owned by the caller.  The library allocates and frees nothing; scratch memory is
+ *     passed in as a workspace.
+ *   - Calls that take a stream only enqueue work on it and return; they never synchronise.
+ *     `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Return value: ADAQP_OK (0) or a negative adaqp_status.  Argument errors are detected on the host
+ *     before anything is launched.  Nothing throws, nothing aborts.
+ *   - Device-side index arrays are trusted to be what adaqp_plan_layout / the caller's partitioner
+ *     produced, but the kernels never touch memory outside the stated extents: a slot whose row index,
+ *     width or offset is out of range is skipped, an edge whose column is out of range is skipped.
+ *   - A count of zero is a successful no-op.
+ *   - Inputs must be finite.  A row's range max - min must be 0 or at least 2^-100 (otherwise the fp32
+ *     reciprocal overflows; codes stay in range but are unspecified).
+ *   - Feature matrices are fp32 row-major with a leading dimension ld >= dim, counted in elements.
+ */
+#ifndef ADAQP_H
+#define ADAQP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum adaqp_status {
+    ADAQP_OK     = 0,
+    ADAQP_EINVAL = -1,  /* NULL pointer with a non-zero count, non-positive dim, ld < dim, negative count, ... */
+    ADAQP_EBITS  = -2,  /* a host-visible bit-width outside {2, 4, 8} */
+    ADAQP_ESIZE  = -3,  /* a declared buffer or workspace is too small, or a size exceeds a documented limit */
+    ADAQP_EHIP   = -4   /* the HIP runtime reported an error (adaqp_last_hip_error gives its text) */
+} adaqp_status;
+
+const char *adaqp_strerror(int status);
+const char *adaqp_last_hip_error(void);     /* text of the last HIP error seen by this thread, "" if none */
+int adaqp_version(void);                    /* major * 10000 + minor * 100 + patch */
+
+/* ---------------------------------------------------------------------------------------------------- */
+/* Buffer layout (host only).  Sec. 5 "Implementation": messages are grouped by assigned bit-width, each   */
+/* group is quantised at one width, the groups are concatenated into one byte array per peer; Sec. 3.3:    */
+/* the buffer sizes follow from the assignment.                                                            */
+/* ---------------------------------------------------------------------------------------------------- */
+
+/* Bytes one packed row occupies: dim codes of `bits` bits, little-endian, padded with zero bits to a whole
+ * number of 32-bit words: 4 * ceil(dim * bits / 32).  Returns -1 for dim <= 0 or bits outside {2,4,8}. */
+int64_t adaqp_row_stride(int32_t dim, int32_t bits);
+
+/* Orders n send slots and sizes the buffers.
+ *   bits_host[n]          width of each slot, in {2, 4, 8}
+ *   peer_of_slot_host[n]  destination peer of each slot, non-decreasing, in [0, n_peers)
+ *   perm_out[n]           perm_out[k] = input slot that becomes sorted slot k.  Order: peer ascending, inside a
+ *                         peer width ascending (2, 4, 8), inside a width the input order (stable).
+ *   row_offset_out[n]     byte offset of sorted slot k in the single concatenated buffer (multiple of 4)
+ *   peer_byte_ptr_out[n_peers + 1]  bytes [ptr[p], ptr[p+1]) go to peer p; ptr[n_peers] = total bytes
+ * The quantise / de-quantise calls take their per-slot arrays (send_idx, bits, row_offset, halo_idx) in
+ * SORTED slot order; the sorted slot index is the "row" that keys the random stream.
+ * Errors: EINVAL (NULL, negative n, dim <= 0, peer order), EBITS. */
+int adaqp_plan_layout(int64_t n, int32_t dim, const uint8_t *bits_host, const int32_t *peer_of_slot_host,
+                      int32_t n_peers, int64_t *perm_out, int64_t *row_offset_out,
+                      int64_t *peer_byte_ptr_out);
+
+/* ---------------------------------------------------------------------------------------------------- */
+/* Send side: Sec. 2.3 Eq. 4 with the stochastic rounding of App. A.1, then sub-byte merging (Sec. 5).    */
+/* ---------------------------------------------------------------------------------------------------- */
+
+/* For each slot s in [0, n_send):  h = feat[send_idx[s], 0:dim],  b = bits[s],  L = 2^b - 1
+ *     Z = min(h) + 0.0f,  range = (max(h) + 0.0f) - Z,  S = range / L,  inv = L / range   (S = inv = 0 if range == 0)
+ *     x_j = min((h_j - Z) * inv, L);  t_j = trunc(x_j * 2^16);  code_j = (t_j + r16(seed, s, j)) >> 16
+ *     params[s] = {Z, S};  code_j is stored in bits [j*b, j*b+b) of the row at packed + row_offset[s]
+ *     (little-endian bit string, zero padded to adaqp_row_stride(dim, b) bytes).
+ * r16(seed, s, j): Philox4x32-10 with key (seed low, seed high) and counter (j / 8, s low, s high,
+ * 0x41645150); its four output words, low half first, give the 16-bit values of columns 8*(j/8) .. +7.
+ * All arithmetic is single fp32 operations in the order written (no fused multiply-add).
+ *
+ *   feat_dev      [n_feat_rows, ld] fp32, read only
+ *   send_idx_dev  [n_send] int32 row of feat per slot;  bits_dev [n_send] uint8;  row_offset_dev [n_send] int64
+ *   packed_dev    [packed_bytes] uint8, written (only the rows' own bytes);  params_dev [n_send][2] fp32, written
+ * Slots with send_idx outside [0, n_feat_rows), bits outside {2,4,8} or a row that does not fit into
+ * packed_bytes are skipped (nothing is written for them).
+ * Errors: EINVAL, EHIP. */
+int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, int64_t ld, int32_t dim,
+                        const int32_t *send_idx_dev, const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                        int64_t n_send, uint64_t seed,
+                        uint8_t *packed_dev, int64_t packed_bytes, float *params_dev, void *stream);
+
+/* ---------------------------------------------------------------------------------------------------- */
+/* Receive side: Sec. 2.3 Eq. 5.  (bits, row_offset, halo_idx) are the receiver's "bit-retrieval index    */
+/* set" of Sec. 5.                                                                                         */
+/* ---------------------------------------------------------------------------------------------------- */
+
+/* For each slot t in [0, n_recv):  feat[halo_idx[t], j] = (float)code_j * S + Z   (product rounded, then sum
+ * rounded), j in [0, dim), with {Z, S} = params[t] and code_j read from packed + row_offset[t].
+ * Columns dim .. ld-1 and rows not listed are left untouched.  Out-of-range slots are skipped as above.
+ * Errors: EINVAL, EHIP. */
+int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
+                         const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                         const int32_t *halo_idx_dev, int64_t n_recv, int32_t dim,
+                         float *feat_dev, int64_t n_feat_rows, int64_t ld, void *stream);
+
+/* ---------------------------------------------------------------------------------------------------- */
+/* Aggregation: Sec. 2.1 Eq. 3, inner sum.  The coefficients alpha(u,v) are the CSR values; the self term  */
+/* is an explicit entry.                                                                                   */
+/* ---------------------------------------------------------------------------------------------------- */
+
+/* Workspace (bytes) adaqp_spmm_csr needs for a launch over `n_rows` rows holding at most `nnz` entries.
+ * Writes *bytes_out (a multiple of 256).  Errors: EINVAL. */
+int adaqp_spmm_workspace_bytes(int64_t n_rows, int64_t nnz, int32_t dim, int64_t *bytes_out);
+
+/* out[v, 0:dim] = sum_{k = rowptr[v]}^{rowptr[v+1]-1} val[k] * H[col[k], 0:dim]   for v in [row_begin, row_end).
+ * fp32 fused multiply-adds; the summation order is fixed by (row range, nnz_range, dim), so repeated calls
+ * give bit-identical results.  Rows without entries give zeros.
+ *
+ *   rowptr_dev [>= row_end + 1] int64 (non-decreasing), col_dev / val_dev [nnz] int32 / fp32
+ *   nnz        length of col_dev and val_dev; no entry index >= nnz is ever read
+ *   nnz_range  number of entries in rows [row_begin, row_end) if the caller knows it, else -1 (nnz is
+ *              used).  It only sizes the launch; the exact count is re-read from rowptr on the device.
+ *   H_dev      [n_cols, ldh] fp32; entries with col outside [0, n_cols) are skipped
+ *   out_dev    [>= row_end, ldo] fp32; only rows [row_begin, row_end), columns [0, dim) are written
+ *   workspace_dev / workspace_bytes   scratch of at least adaqp_spmm_workspace_bytes(row_end - row_begin,
+ *              nnz_range or nnz, dim) bytes, 256-byte aligned; contents need not be initialised and are
+ *              undefined afterwards.  Two launches that may run concurrently need distinct workspaces.
+ * Errors: EINVAL, ESIZE (workspace too small), EHIP. */
+int adaqp_spmm_csr(const int64_t *rowptr_dev, const int32_t *col_dev, const float *val_dev, int64_t nnz,
+                   int64_t row_begin, int64_t row_end, int64_t nnz_range,
+                   const float *H_dev, int64_t n_cols, int64_t ldh, int32_t dim,
+                   float *out_dev, int64_t ldo,
+                   void *workspace_dev, int64_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------------- */
+/* One layer's aggregation step with the message path overlapped (Sec. 3.1, Sec. 3.4 Fig. 7).             */
+/* ---------------------------------------------------------------------------------------------------- */
+
+typedef enum adaqp_schedule {
+    ADAQP_SERIAL   = 0, /* everything on stream_msg in program order */
+    ADAQP_ISOLATED = 1, /* Fig. 7: the overlapped SpMM starts only once quantisation has finished, so it
+                           overlaps the transfer (here: the loop-back copy) and nothing else by design */
+    ADAQP_FREE     = 2  /* the overlapped SpMM starts at once on stream_agg and may overlap quantisation */
+} adaqp_schedule;
+
+typedef enum adaqp_direction {
+    ADAQP_FORWARD  = 0, /* quantise send rows of `feat`, loop back, de-quantise into halo rows of `feat`,
+                           aggregate: overlap_rows (central) on stream_agg, dependent_rows (marginal) after
+                           the de-quantisation */
+    ADAQP_BACKWARD = 1  /* the CSR is the transposed graph and `feat` holds the output gradients: aggregate
+                           dependent_rows (halo rows of A^T dY) first, quantise + pack them from `out`,
+                           loop back; overlap_rows (local rows) on stream_agg */
+} adaqp_direction;
+
+typedef struct adaqp_layer_desc {
+    int32_t direction;          /* adaqp_direction */
+    int32_t schedule;           /* adaqp_schedule */
+    /* graph */
+    const int64_t *rowptr_dev;
+    const int32_t *col_dev;
+    const float   *val_dev;
+    int64_t nnz;
+    int64_t overlap_begin, overlap_end, overlap_nnz;        /* rows that do not depend on received messages */
+    int64_t dependent_begin, dependent_end, dependent_nnz;  /* rows that do (forward) / that are sent (backward) */
+    /* dense operands */
+    float  *feat_dev;           /* forward: [n_feat_rows, ld], halo rows are overwritten; backward: dY, read only */
+    int64_t n_feat_rows, ld;
+    int32_t dim;
+    float  *out_dev;            /* aggregation result, [>= max(overlap_end, dependent_end), ldo] */
+    int64_t ldo;
+    /* message path, all per-slot arrays in sorted slot order */
+    const int32_t *send_idx_dev;    /* forward: rows of feat; backward: rows of out */
+    const uint8_t *bits_dev;
+    const int64_t *row_offset_dev;
+    const int32_t *halo_idx_dev;    /* forward only: destination rows of the received slots */
+    int64_t n_send;
+    uint64_t seed;
+    uint8_t *packed_dev;   float *params_dev;           /* send buffers */
+    uint8_t *recv_packed_dev; float *recv_params_dev;   /* receive buffers; the loop-back copy stands in for the exchange */
+    int64_t packed_bytes;
+    /* scratch and streams */
+    void *workspace_overlap_dev;   int64_t workspace_overlap_bytes;
+    void *workspace_dependent_dev; int64_t workspace_dependent_bytes;
+    void *stream_msg;           /* message path and dependent aggregation */
+    void *stream_agg;           /* overlapped aggregation; joined back into stream_msg before returning */
+    void *event_fork;           /* two hipEvent_t created by the caller (timing may be disabled) */
+    void *event_join;
+} adaqp_layer_desc;
+
+/* Enqueues one layer step.  On return all work has been enqueued and stream_msg has been made to wait for
+ * stream_agg, so synchronising stream_msg completes the step.  The three schedules give bit-identical
+ * results.  Errors: EINVAL, ESIZE, EHIP. */
+int adaqp_layer_step(const adaqp_layer_desc *desc_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAQP_H */

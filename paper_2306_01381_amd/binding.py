@@ -1,0 +1,185 @@
+"""Thin ctypes binding of libadaqp.so (include/adaqp.h).  Argument marshalling only.
+
+Every function has the name of the C entry point it calls.  Tensors are torch tensors that already live
+where the C function expects them (device tensors for *_dev arguments, numpy arrays for the host-only
+layout call); torch supplies device memory and streams and nothing else.  There is no fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libadaqp.so")
+
+OK, EINVAL, EBITS, ESIZE, EHIP = 0, -1, -2, -3, -4
+SERIAL, ISOLATED, FREE = 0, 1, 2
+FORWARD, BACKWARD = 0, 1
+
+_i64, _i32, _u64, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_void_p
+
+
+class AdaqpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        L = lib()
+        msg = L.adaqp_strerror(status).decode()
+        if status == EHIP:
+            msg += ": " + L.adaqp_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+class LayerDesc(ctypes.Structure):
+    """Mirror of struct adaqp_layer_desc."""
+    _fields_ = [
+        ("direction", _i32), ("schedule", _i32),
+        ("rowptr_dev", _vp), ("col_dev", _vp), ("val_dev", _vp), ("nnz", _i64),
+        ("overlap_begin", _i64), ("overlap_end", _i64), ("overlap_nnz", _i64),
+        ("dependent_begin", _i64), ("dependent_end", _i64), ("dependent_nnz", _i64),
+        ("feat_dev", _vp), ("n_feat_rows", _i64), ("ld", _i64), ("dim", _i32),
+        ("out_dev", _vp), ("ldo", _i64),
+        ("send_idx_dev", _vp), ("bits_dev", _vp), ("row_offset_dev", _vp), ("halo_idx_dev", _vp),
+        ("n_send", _i64), ("seed", _u64),
+        ("packed_dev", _vp), ("params_dev", _vp), ("recv_packed_dev", _vp), ("recv_params_dev", _vp),
+        ("packed_bytes", _i64),
+        ("workspace_overlap_dev", _vp), ("workspace_overlap_bytes", _i64),
+        ("workspace_dependent_dev", _vp), ("workspace_dependent_bytes", _i64),
+        ("stream_msg", _vp), ("stream_agg", _vp), ("event_fork", _vp), ("event_join", _vp),
+    ]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+_SIGNATURES = {
+    "adaqp_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "adaqp_last_hip_error": (ctypes.c_char_p, []),
+    "adaqp_version": (ctypes.c_int, []),
+    "adaqp_row_stride": (_i64, [_i32, _i32]),
+    "adaqp_plan_layout": (ctypes.c_int, [_i64, _i32, _vp, _vp, _i32, _vp, _vp, _vp]),
+    "adaqp_quantize_pack": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _u64, _vp, _i64, _vp, _vp]),
+    "adaqp_unpack_dequant": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i64, _vp]),
+    "adaqp_spmm_workspace_bytes": (ctypes.c_int, [_i64, _i64, _i32, ctypes.POINTER(_i64)]),
+    "adaqp_spmm_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
+                                      _vp, _i64, _vp, _i64, _vp]),
+    "adaqp_layer_step": (ctypes.c_int, [ctypes.POINTER(LayerDesc)]),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the in-tree library; raises if it has not been built (python -m paper_2306_01381_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2306_01381_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise AdaqpError(status, where)
+
+
+def _dev(t: Optional[torch.Tensor], dtype: torch.dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise TypeError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _matrix(t: torch.Tensor, name: str) -> Tuple[int, int, int]:
+    """(pointer, rows, leading dimension) of a 2-D fp32 device tensor whose rows are contiguous."""
+    if not t.is_cuda or t.dtype != torch.float32 or t.dim() != 2 or t.stride(1) != 1:
+        raise TypeError(f"{name} must be a 2-D fp32 device tensor with unit column stride")
+    return t.data_ptr(), t.shape[0], t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def adaqp_version() -> int:
+    return lib().adaqp_version()
+
+
+def adaqp_row_stride(dim: int, bits: int) -> int:
+    return int(lib().adaqp_row_stride(dim, bits))
+
+
+def adaqp_plan_layout(dim: int, bits_host: np.ndarray, peer_of_slot_host: np.ndarray, n_peers: int):
+    """Host-only.  Returns (perm, row_offset, peer_byte_ptr) as int64 numpy arrays."""
+    bits = np.ascontiguousarray(bits_host, dtype=np.uint8)
+    peer = np.ascontiguousarray(peer_of_slot_host, dtype=np.int32)
+    n = bits.shape[0]
+    if peer.shape[0] != n:
+        raise ValueError("bits and peer_of_slot differ in length")
+    perm = np.zeros(n, dtype=np.int64)
+    off = np.zeros(n, dtype=np.int64)
+    pbp = np.zeros(max(n_peers, 0) + 1, dtype=np.int64)
+    _check(lib().adaqp_plan_layout(n, dim, bits.ctypes.data, peer.ctypes.data, n_peers,
+                                   perm.ctypes.data, off.ctypes.data, pbp.ctypes.data), "adaqp_plan_layout")
+    return perm, off, pbp
+
+
+def adaqp_quantize_pack(feat: torch.Tensor, dim: int, send_idx: torch.Tensor, bits: torch.Tensor,
+                        row_offset: torch.Tensor, seed: int, packed: torch.Tensor, params: torch.Tensor,
+                        stream: Optional[torch.cuda.Stream] = None) -> None:
+    fp, n_rows, ld = _matrix(feat, "feat")
+    n = send_idx.shape[0]
+    _check(lib().adaqp_quantize_pack(fp, n_rows, ld, dim, _dev(send_idx, torch.int32, "send_idx"),
+                                     _dev(bits, torch.uint8, "bits"), _dev(row_offset, torch.int64, "row_offset"),
+                                     n, seed & (2**64 - 1), _dev(packed, torch.uint8, "packed"), packed.numel(),
+                                     _dev(params, torch.float32, "params"), _stream(stream)),
+           "adaqp_quantize_pack")
+
+
+def adaqp_unpack_dequant(packed: torch.Tensor, params: torch.Tensor, bits: torch.Tensor,
+                         row_offset: torch.Tensor, halo_idx: torch.Tensor, dim: int, feat: torch.Tensor,
+                         stream: Optional[torch.cuda.Stream] = None) -> None:
+    fp, n_rows, ld = _matrix(feat, "feat")
+    n = halo_idx.shape[0]
+    _check(lib().adaqp_unpack_dequant(_dev(packed, torch.uint8, "packed"), packed.numel(),
+                                      _dev(params, torch.float32, "params"), _dev(bits, torch.uint8, "bits"),
+                                      _dev(row_offset, torch.int64, "row_offset"),
+                                      _dev(halo_idx, torch.int32, "halo_idx"), n, dim, fp, n_rows, ld,
+                                      _stream(stream)),
+           "adaqp_unpack_dequant")
+
+
+def adaqp_spmm_workspace_bytes(n_rows: int, nnz: int, dim: int) -> int:
+    out = _i64(0)
+    _check(lib().adaqp_spmm_workspace_bytes(n_rows, nnz, dim, ctypes.byref(out)), "adaqp_spmm_workspace_bytes")
+    return int(out.value)
+
+
+def adaqp_spmm_csr(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, row_begin: int, row_end: int,
+                   H: torch.Tensor, dim: int, out: torch.Tensor, workspace: torch.Tensor,
+                   nnz_range: int = -1, stream: Optional[torch.cuda.Stream] = None) -> None:
+    hp, n_cols, ldh = _matrix(H, "H")
+    op, _, ldo = _matrix(out, "out")
+    _check(lib().adaqp_spmm_csr(_dev(rowptr, torch.int64, "rowptr"), _dev(col, torch.int32, "col"),
+                                _dev(val, torch.float32, "val"), col.numel(), row_begin, row_end, nnz_range,
+                                hp, n_cols, ldh, dim, op, ldo, _dev(workspace, torch.uint8, "workspace"),
+                                workspace.numel(), _stream(stream)),
+           "adaqp_spmm_csr")
+
+
+def adaqp_layer_step(desc: LayerDesc) -> None:
+    _check(lib().adaqp_layer_step(ctypes.byref(desc)), "adaqp_layer_step")

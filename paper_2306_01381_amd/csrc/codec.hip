@@ -1,0 +1,465 @@
+// Message codec for gfx950: quantise + pack (Sec. 2.3 Eq. 4, App. A.1, Sec. 5 "Implementation") and
+// unpack + de-quantise (Sec. 2.3 Eq. 5).
+//
+// Both kernels are HBM-streaming: the send side reads 4*dim bytes per slot and writes dim*b/8, the receive
+// side does the reverse.  Nothing is a dense contraction, so the matrix cores are not used.
+//
+// Send side, one pass over memory.  A row of dim floats is cut into "granules" of 8 consecutive columns;
+// a granule is the unit of everything: 32 bytes of input (two 16-byte loads), one Philox4x32-10 call (its
+// 128 bits are the eight 16-bit rounding values), b bytes of output.  A row is owned by LPR = 2^k lanes of
+// a wave, lane l holding granules l, l + LPR, l + 2*LPR, ... (GPL of them) in registers, so that at each
+// step the LPR lanes of a row read LPR*32 contiguous bytes.  min / max are reduced over the row's lanes
+// with xor shuffles, the row's (Z, S, inv) are computed redundantly by every lane, and the codes are packed
+// in registers.  LPR and GPL are chosen on the host so that LPR*GPL barely exceeds dim/8 (D=602: 16 x 5,
+// D=256: 8 x 4, D=300: 8 x 5, D=128: 4 x 4); a wave therefore carries 64/LPR rows.
+//
+// fp32 arithmetic is written operation by operation and the file is compiled with -ffp-contract=off: the
+// integer codes depend on every rounding.
+#include "common.hpp"
+
+namespace adaqp {
+namespace {
+
+// ---------------------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  The key schedule is wave-uniform (it only depends on the seed).
+// ---------------------------------------------------------------------------------------------------------
+struct Rand128 { uint32_t w0, w1, w2, w3; };
+
+__device__ __forceinline__ Rand128 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1)
+{
+    constexpr uint32_t kMulA = 0xD2511F53u, kMulB = 0xCD9E8D57u;
+    constexpr uint32_t kWeylA = 0x9E3779B9u, kWeylB = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hiA = __umulhi(kMulA, c0), loA = kMulA * c0;
+        const uint32_t hiB = __umulhi(kMulB, c2), loB = kMulB * c2;
+        c0 = hiB ^ c1 ^ k0;
+        c1 = loB;
+        c2 = hiA ^ c3 ^ k1;
+        c3 = loA;
+        k0 += kWeylA;
+        k1 += kWeylB;
+    }
+    return Rand128{c0, c1, c2, c3};
+}
+
+constexpr uint32_t kCounterTag = 0x41645150u;
+
+struct QuantArgs {
+    const float *feat;
+    int64_t n_feat_rows, ld;
+    int32_t dim, n_granules;
+    const int32_t *send_idx;
+    const uint8_t *bits;
+    const int64_t *row_offset;
+    int64_t n_send;
+    uint32_t seed_lo, seed_hi;
+    uint8_t *packed;
+    int64_t packed_bytes;
+    float *params;
+    int32_t lpr_log2;
+};
+
+template <int VW> struct VecOf;
+template <> struct VecOf<1> { using type = float; };
+template <> struct VecOf<2> { using type = float2; };
+template <> struct VecOf<4> { using type = float4; };
+
+template <int VW>
+__device__ __forceinline__ void load_vec(const float *p, float *dst)
+{
+    using V = typename VecOf<VW>::type;
+    const V v = *reinterpret_cast<const V *>(p);
+    if constexpr (VW == 1) { dst[0] = v; }
+    if constexpr (VW == 2) { dst[0] = v.x; dst[1] = v.y; }
+    if constexpr (VW == 4) { dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w; }
+}
+
+template <int VW>
+__device__ __forceinline__ void store_vec(float *p, const float *src)
+{
+    using V = typename VecOf<VW>::type;
+    if constexpr (VW == 1) { *p = src[0]; }
+    if constexpr (VW == 2) { *reinterpret_cast<V *>(p) = make_float2(src[0], src[1]); }
+    if constexpr (VW == 4) { *reinterpret_cast<V *>(p) = make_float4(src[0], src[1], src[2], src[3]); }
+}
+
+// Codes of one granule (8 columns) at width B, merged little-endian into lo (and hi for B == 8).
+template <int B>
+__device__ __forceinline__ void quantise_granule(const float (&x)[8], float Z, float inv, float levels,
+                                                 const Rand128 &rnd, int32_t col0, int32_t dim,
+                                                 uint32_t &lo, uint32_t &hi)
+{
+    const uint32_t words[4] = {rnd.w0, rnd.w1, rnd.w2, rnd.w3};
+    lo = 0u;
+    hi = 0u;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float pos = (x[k] - Z) * inv;                         // Eq. 4 argument, >= 0
+        pos = fminf(pos, levels);                             // the top element may overshoot by an ulp
+        const uint32_t fixed = (uint32_t)(pos * 65536.0f);    // 16.16 fixed point, truncated
+        const uint32_t r16 = (k & 1) ? (words[k >> 1] >> 16) : (words[k >> 1] & 0xFFFFu);
+        uint32_t code = (fixed + r16) >> 16;                  // App. A.1: up with probability frac
+        code = (col0 + k < dim) ? code : 0u;                  // padding bits are zero
+        if (B * k < 32) lo |= code << ((B * k) & 31);
+        else            hi |= code << ((B * k) & 31);
+    }
+}
+
+template <int B>
+__device__ __forceinline__ void store_granule(uint8_t *row, int32_t g, int32_t n_granules, int64_t stride,
+                                              uint32_t lo, uint32_t hi)
+{
+    if constexpr (B == 2) {
+        *reinterpret_cast<uint16_t *>(row + 2 * (int64_t)g) = (uint16_t)lo;
+        if (g == n_granules - 1 && 2 * (int64_t)(g + 1) < stride)       // odd granule count: two pad bytes
+            *reinterpret_cast<uint16_t *>(row + 2 * (int64_t)(g + 1)) = (uint16_t)0;
+    }
+    if constexpr (B == 4) {
+        *reinterpret_cast<uint32_t *>(row + 4 * (int64_t)g) = lo;
+    }
+    if constexpr (B == 8) {
+        *reinterpret_cast<uint32_t *>(row + 8 * (int64_t)g) = lo;
+        if (8 * (int64_t)g + 4 < stride) *reinterpret_cast<uint32_t *>(row + 8 * (int64_t)g + 4) = hi;
+    }
+}
+
+struct RowScale { float Z, S, inv; };
+
+__device__ __forceinline__ RowScale row_scale(float mn, float mx, float levels)
+{
+    RowScale rs;
+    rs.Z = mn + 0.0f;                     // -0 -> +0, so that any reduction order gives the same zero-point
+    const float range = (mx + 0.0f) - rs.Z;
+    rs.S = 0.0f;
+    rs.inv = 0.0f;
+    if (range > 0.0f) {
+        rs.S = range / levels;            // Eq. 4 scale, correctly rounded fp32 division
+        rs.inv = levels / range;
+    }
+    return rs;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Register-resident rows: GPL granules per lane, LPR = 2^lpr_log2 lanes per row.
+// ---------------------------------------------------------------------------------------------------------
+template <int GPL, int VW>
+__global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int lpr = 1 << a.lpr_log2;
+    const int rows_per_wave = kWave >> a.lpr_log2;
+    const int64_t s = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * rows_per_wave + (lane >> a.lpr_log2);
+    const int l = lane & (lpr - 1);
+
+    bool active = s < a.n_send;
+    int32_t r = 0, b = 0;
+    int64_t off = 0;
+    if (active) {
+        r = a.send_idx[s];
+        b = a.bits[s];
+        off = a.row_offset[s];
+    }
+    const int64_t stride = 4 * (((int64_t)a.dim * b + 31) >> 5);
+    active = active && r >= 0 && r < a.n_feat_rows && (b == 2 || b == 4 || b == 8) && off >= 0 &&
+             (off & 3) == 0 && off + stride <= a.packed_bytes;
+    const float *h = a.feat + (active ? (int64_t)r * a.ld : 0);
+
+    // gather: the row's granules l, l+LPR, ... into registers; columns past dim repeat the first element,
+    // which leaves min and max alone
+    float x[GPL][8];
+    const float first = active ? h[0] : 0.0f;
+#pragma unroll
+    for (int i = 0; i < GPL; ++i) {
+        const int32_t c0 = (i * lpr + l) * 8;
+#pragma unroll
+        for (int v = 0; v < 8 / VW; ++v) {
+            const int32_t c = c0 + v * VW;
+            if (active && c < a.dim) {
+                load_vec<VW>(h + c, &x[i][v * VW]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < VW; ++k) x[i][v * VW + k] = first;
+            }
+        }
+    }
+
+    float mn = first, mx = first;
+#pragma unroll
+    for (int i = 0; i < GPL; ++i)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            mn = fminf(mn, x[i][k]);
+            mx = fmaxf(mx, x[i][k]);
+        }
+    for (int m = 1; m < lpr; m <<= 1) {
+        mn = fminf(mn, __shfl_xor(mn, m, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, m, kWave));
+    }
+    if (!active) return;                                   // no cross-lane operation below this line
+
+    const float levels = (float)((1 << b) - 1);
+    const RowScale rs = row_scale(mn, mx, levels);
+    if (l == 0) *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
+
+    uint8_t *row = a.packed + off;
+    const uint32_t s_lo = (uint32_t)s, s_hi = (uint32_t)((uint64_t)s >> 32);
+#pragma unroll
+    for (int i = 0; i < GPL; ++i) {
+        const int32_t g = i * lpr + l;
+        if (g < a.n_granules) {
+            const Rand128 rnd = philox4x32_10((uint32_t)g, s_lo, s_hi, kCounterTag, a.seed_lo, a.seed_hi);
+            uint32_t lo, hi;
+            if (b == 4) {
+                quantise_granule<4>(x[i], rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
+                store_granule<4>(row, g, a.n_granules, stride, lo, hi);
+            } else if (b == 2) {
+                quantise_granule<2>(x[i], rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
+                store_granule<2>(row, g, a.n_granules, stride, lo, hi);
+            } else {
+                quantise_granule<8>(x[i], rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
+                store_granule<8>(row, g, a.n_granules, stride, lo, hi);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Rows too wide for registers (dim > 8 * 64 * kMaxGpl): one wave per row, two passes over the row (the
+// second one is served by the caches).
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void quantize_pack_wide_kernel(const QuantArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t s = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);     // wave-uniform
+    if (s >= a.n_send) return;
+    const int32_t r = a.send_idx[s];
+    const int32_t b = a.bits[s];
+    const int64_t off = a.row_offset[s];
+    const int64_t stride = 4 * (((int64_t)a.dim * b + 31) >> 5);
+    if (!(r >= 0 && r < a.n_feat_rows && (b == 2 || b == 4 || b == 8) && off >= 0 && (off & 3) == 0 &&
+          off + stride <= a.packed_bytes))
+        return;
+    const float *h = a.feat + (int64_t)r * a.ld;
+
+    float mn = h[0], mx = mn;
+    for (int32_t c = lane; c < a.dim; c += kWave) {
+        const float v = h[c];
+        mn = fminf(mn, v);
+        mx = fmaxf(mx, v);
+    }
+    for (int m = 1; m < kWave; m <<= 1) {
+        mn = fminf(mn, __shfl_xor(mn, m, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, m, kWave));
+    }
+    const float levels = (float)((1 << b) - 1);
+    const RowScale rs = row_scale(mn, mx, levels);
+    if (lane == 0) *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
+
+    uint8_t *row = a.packed + off;
+    const uint32_t s_lo = (uint32_t)s, s_hi = (uint32_t)((uint64_t)s >> 32);
+    for (int32_t g = lane; g < a.n_granules; g += kWave) {
+        float x[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) x[k] = (g * 8 + k < a.dim) ? h[g * 8 + k] : mn;
+        const Rand128 rnd = philox4x32_10((uint32_t)g, s_lo, s_hi, kCounterTag, a.seed_lo, a.seed_hi);
+        uint32_t lo, hi;
+        if (b == 4) {
+            quantise_granule<4>(x, rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
+            store_granule<4>(row, g, a.n_granules, stride, lo, hi);
+        } else if (b == 2) {
+            quantise_granule<2>(x, rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
+            store_granule<2>(row, g, a.n_granules, stride, lo, hi);
+        } else {
+            quantise_granule<8>(x, rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
+            store_granule<8>(row, g, a.n_granules, stride, lo, hi);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Receive side: one wave per slot; a lane turns VW consecutive codes into VW floats and stores them as one
+// vector, so a wave writes 64*VW*4 contiguous bytes per step.  VW*b divides 32, so the codes of one vector
+// never straddle a 32-bit word of the packed row.
+// ---------------------------------------------------------------------------------------------------------
+struct DequantArgs {
+    const uint8_t *packed;
+    int64_t packed_bytes;
+    const float *params;
+    const uint8_t *bits;
+    const int64_t *row_offset;
+    const int32_t *halo_idx;
+    int64_t n_recv;
+    int32_t dim;
+    float *feat;
+    int64_t n_feat_rows, ld;
+};
+
+template <int VW>
+__global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(const DequantArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t t = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);     // wave-uniform
+    if (t >= a.n_recv) return;
+    const int32_t r = a.halo_idx[t];
+    const int32_t b = a.bits[t];
+    const int64_t off = a.row_offset[t];
+    const int64_t stride = 4 * (((int64_t)a.dim * b + 31) >> 5);
+    if (!(r >= 0 && r < a.n_feat_rows && (b == 2 || b == 4 || b == 8) && off >= 0 && (off & 3) == 0 &&
+          off + stride <= a.packed_bytes))
+        return;
+    const float2 zs = *reinterpret_cast<const float2 *>(a.params + 2 * t);
+    const float Z = zs.x, S = zs.y;
+    const uint32_t *words = reinterpret_cast<const uint32_t *>(a.packed + off);
+    float *h = a.feat + (int64_t)r * a.ld;
+    const uint32_t mask = (1u << b) - 1u;
+
+    for (int32_t c = lane * VW; c < a.dim; c += kWave * VW) {
+        const uint32_t bit = (uint32_t)c * (uint32_t)b;
+        const uint32_t w = words[bit >> 5] >> (bit & 31u);
+        float y[VW];
+#pragma unroll
+        for (int k = 0; k < VW; ++k) {
+            const uint32_t code = (w >> (k * b)) & mask;
+            const float scaled = (float)code * S;          // Eq. 5: product rounded, then sum rounded
+            y[k] = scaled + Z;
+        }
+        store_vec<VW>(h + c, y);
+    }
+}
+
+constexpr int kMaxGpl = 8;
+
+// Largest vector width (floats) such that every row start and every vector inside a row is naturally aligned.
+int vector_width(const void *base, int64_t ld, int32_t dim)
+{
+    if (dim % 4 == 0 && ld % 4 == 0 && aligned_to(base, 16)) return 4;
+    if (dim % 2 == 0 && ld % 2 == 0 && aligned_to(base, 8)) return 2;
+    return 1;
+}
+
+template <int VW>
+hipError_t launch_quantize(const QuantArgs &a, int gpl, dim3 grid, hipStream_t st)
+{
+    switch (gpl) {
+#define ADAQP_CASE(G) case G: hipLaunchKernelGGL((quantize_pack_kernel<G, VW>), grid, dim3(kBlock), 0, st, a); break;
+        ADAQP_CASE(1) ADAQP_CASE(2) ADAQP_CASE(3) ADAQP_CASE(4)
+        ADAQP_CASE(5) ADAQP_CASE(6) ADAQP_CASE(7) ADAQP_CASE(8)
+#undef ADAQP_CASE
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+}  // namespace adaqp
+
+using namespace adaqp;
+
+extern "C" int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, int64_t ld, int32_t dim,
+                                   const int32_t *send_idx_dev, const uint8_t *bits_dev,
+                                   const int64_t *row_offset_dev, int64_t n_send, uint64_t seed,
+                                   uint8_t *packed_dev, int64_t packed_bytes, float *params_dev, void *stream)
+{
+    if (n_send < 0 || dim <= 0 || ld < dim || n_feat_rows < 0 || packed_bytes < 0) return ADAQP_EINVAL;
+    if (n_send == 0) return ADAQP_OK;
+    if (!feat_dev || !send_idx_dev || !bits_dev || !row_offset_dev || !packed_dev || !params_dev)
+        return ADAQP_EINVAL;
+    if (n_feat_rows == 0) return ADAQP_EINVAL;
+    if (!aligned_to(feat_dev, 4) || !aligned_to(params_dev, 8) || !aligned_to(packed_dev, 4) ||
+        !aligned_to(send_idx_dev, 4) || !aligned_to(row_offset_dev, 8))
+        return ADAQP_EINVAL;
+    if (n_send > ((int64_t)1 << 40)) return ADAQP_ESIZE;
+
+    QuantArgs a;
+    a.feat = feat_dev;
+    a.n_feat_rows = n_feat_rows;
+    a.ld = ld;
+    a.dim = dim;
+    a.n_granules = (dim + 7) / 8;
+    a.send_idx = send_idx_dev;
+    a.bits = bits_dev;
+    a.row_offset = row_offset_dev;
+    a.n_send = n_send;
+    a.seed_lo = (uint32_t)seed;
+    a.seed_hi = (uint32_t)(seed >> 32);
+    a.packed = packed_dev;
+    a.packed_bytes = packed_bytes;
+    a.params = params_dev;
+    a.lpr_log2 = 0;
+    hipStream_t st = (hipStream_t)stream;
+
+    // lanes per row / granules per lane: least padding first, then the most granules per lane
+    int best_k = -1, best_gpl = 0;
+    int64_t best_waste = INT64_MAX;
+    for (int k = 0; k <= 6; ++k) {
+        const int lpr = 1 << k;
+        const int gpl = (a.n_granules + lpr - 1) / lpr;
+        if (gpl > kMaxGpl) continue;
+        const int64_t waste = (int64_t)lpr * gpl - a.n_granules;
+        if (waste < best_waste || (waste == best_waste && gpl <= 5 && gpl > best_gpl)) {
+            best_waste = waste;
+            best_k = k;
+            best_gpl = gpl;
+        }
+    }
+    if (best_k < 0) {
+        const int64_t blocks = (n_send + kWavesPerBlock - 1) / kWavesPerBlock;
+        if (blocks > INT32_MAX) return ADAQP_ESIZE;
+        hipLaunchKernelGGL(quantize_pack_wide_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+        ADAQP_HIP_TRY(hipGetLastError());
+        return ADAQP_OK;
+    }
+    a.lpr_log2 = best_k;
+    const int64_t rows_per_block = (int64_t)kWavesPerBlock * (kWave >> best_k);
+    const int64_t blocks = (n_send + rows_per_block - 1) / rows_per_block;
+    if (blocks > INT32_MAX) return ADAQP_ESIZE;
+    const dim3 grid((unsigned)blocks);
+    const int vw = vector_width(feat_dev, ld, dim);
+    hipError_t err;
+    if (vw == 4) err = launch_quantize<4>(a, best_gpl, grid, st);
+    else if (vw == 2) err = launch_quantize<2>(a, best_gpl, grid, st);
+    else err = launch_quantize<1>(a, best_gpl, grid, st);
+    ADAQP_HIP_TRY(err);
+    return ADAQP_OK;
+}
+
+extern "C" int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
+                                    const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                                    const int32_t *halo_idx_dev, int64_t n_recv, int32_t dim,
+                                    float *feat_dev, int64_t n_feat_rows, int64_t ld, void *stream)
+{
+    if (n_recv < 0 || dim <= 0 || ld < dim || n_feat_rows < 0 || packed_bytes < 0) return ADAQP_EINVAL;
+    if (n_recv == 0) return ADAQP_OK;
+    if (!packed_dev || !params_dev || !bits_dev || !row_offset_dev || !halo_idx_dev || !feat_dev)
+        return ADAQP_EINVAL;
+    if (n_feat_rows == 0) return ADAQP_EINVAL;
+    if (!aligned_to(feat_dev, 4) || !aligned_to(params_dev, 8) || !aligned_to(packed_dev, 4) ||
+        !aligned_to(halo_idx_dev, 4) || !aligned_to(row_offset_dev, 8))
+        return ADAQP_EINVAL;
+    const int64_t blocks = (n_recv + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > INT32_MAX) return ADAQP_ESIZE;
+
+    DequantArgs a;
+    a.packed = packed_dev;
+    a.packed_bytes = packed_bytes;
+    a.params = params_dev;
+    a.bits = bits_dev;
+    a.row_offset = row_offset_dev;
+    a.halo_idx = halo_idx_dev;
+    a.n_recv = n_recv;
+    a.dim = dim;
+    a.feat = feat_dev;
+    a.n_feat_rows = n_feat_rows;
+    a.ld = ld;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid((unsigned)blocks);
+    const int vw = vector_width(feat_dev, ld, dim);
+    if (vw == 4) hipLaunchKernelGGL(unpack_dequant_kernel<4>, grid, dim3(kBlock), 0, st, a);
+    else if (vw == 2) hipLaunchKernelGGL(unpack_dequant_kernel<2>, grid, dim3(kBlock), 0, st, a);
+    else hipLaunchKernelGGL(unpack_dequant_kernel<1>, grid, dim3(kBlock), 0, st, a);
+    ADAQP_HIP_TRY(hipGetLastError());
+    return ADAQP_OK;
+}

@@ -1,0 +1,230 @@
+// Host side of libadaqp: status strings, the buffer layout of Sec. 5 "Implementation" (messages grouped by
+// bit-width, groups concatenated per peer) and the layer step that overlaps the message path with the
+// aggregation of the rows that do not depend on it (Sec. 3.1, Sec. 3.4 Fig. 7).
+#include <stdio.h>
+#include <string.h>
+
+#include "common.hpp"
+
+namespace adaqp {
+
+static thread_local char g_hip_error[256] = "";
+
+int note_hip_error(hipError_t err, const char *what)
+{
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(err));
+    return ADAQP_EHIP;
+}
+
+}  // namespace adaqp
+
+using namespace adaqp;
+
+extern "C" const char *adaqp_strerror(int status)
+{
+    switch (status) {
+        case ADAQP_OK: return "ok";
+        case ADAQP_EINVAL: return "invalid argument";
+        case ADAQP_EBITS: return "bit-width outside {2, 4, 8}";
+        case ADAQP_ESIZE: return "buffer or workspace too small, or size beyond a documented limit";
+        case ADAQP_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+extern "C" const char *adaqp_last_hip_error(void) { return g_hip_error; }
+
+extern "C" int adaqp_version(void) { return 100; }
+
+extern "C" int64_t adaqp_row_stride(int32_t dim, int32_t bits)
+{
+    if (dim <= 0 || !valid_bits(bits)) return -1;
+    return 4 * (((int64_t)dim * bits + 31) / 32);
+}
+
+extern "C" int adaqp_plan_layout(int64_t n, int32_t dim, const uint8_t *bits_host,
+                                 const int32_t *peer_of_slot_host, int32_t n_peers, int64_t *perm_out,
+                                 int64_t *row_offset_out, int64_t *peer_byte_ptr_out)
+{
+    if (n < 0 || dim <= 0 || n_peers < 0 || !peer_byte_ptr_out) return ADAQP_EINVAL;
+    if (n > 0 && (!bits_host || !peer_of_slot_host || !perm_out || !row_offset_out)) return ADAQP_EINVAL;
+    if (n > 0 && n_peers == 0) return ADAQP_EINVAL;
+    for (int64_t i = 0; i < n; ++i) {
+        if (!valid_bits(bits_host[i])) return ADAQP_EBITS;
+        const int32_t p = peer_of_slot_host[i];
+        if (p < 0 || p >= n_peers) return ADAQP_EINVAL;
+        if (i > 0 && p < peer_of_slot_host[i - 1]) return ADAQP_EINVAL;
+    }
+    // One counting pass per peer segment: slots of width 2 first, then 4, then 8, input order kept.
+    const int64_t stride_of[3] = {adaqp_row_stride(dim, 2), adaqp_row_stride(dim, 4), adaqp_row_stride(dim, 8)};
+    int64_t seg_begin = 0, bytes = 0;
+    for (int32_t p = 0; p < n_peers; ++p) {
+        int64_t seg_end = seg_begin;
+        int64_t count[3] = {0, 0, 0};
+        while (seg_end < n && peer_of_slot_host[seg_end] == p) {
+            const int w = bits_host[seg_end] == 2 ? 0 : (bits_host[seg_end] == 4 ? 1 : 2);
+            ++count[w];
+            ++seg_end;
+        }
+        peer_byte_ptr_out[p] = bytes;
+        int64_t next_slot[3], next_byte[3];
+        next_slot[0] = seg_begin;
+        next_slot[1] = next_slot[0] + count[0];
+        next_slot[2] = next_slot[1] + count[1];
+        next_byte[0] = bytes;
+        next_byte[1] = next_byte[0] + count[0] * stride_of[0];
+        next_byte[2] = next_byte[1] + count[1] * stride_of[1];
+        bytes = next_byte[2] + count[2] * stride_of[2];
+        for (int64_t i = seg_begin; i < seg_end; ++i) {
+            const int w = bits_host[i] == 2 ? 0 : (bits_host[i] == 4 ? 1 : 2);
+            const int64_t k = next_slot[w]++;
+            perm_out[k] = i;
+            row_offset_out[k] = next_byte[w];
+            next_byte[w] += stride_of[w];
+        }
+        seg_begin = seg_end;
+    }
+    peer_byte_ptr_out[n_peers] = bytes;
+    return ADAQP_OK;
+}
+
+namespace {
+
+int check_desc(const adaqp_layer_desc *d)
+{
+    if (!d) return ADAQP_EINVAL;
+    if (d->direction != ADAQP_FORWARD && d->direction != ADAQP_BACKWARD) return ADAQP_EINVAL;
+    if (d->schedule != ADAQP_SERIAL && d->schedule != ADAQP_ISOLATED && d->schedule != ADAQP_FREE)
+        return ADAQP_EINVAL;
+    if (d->dim <= 0 || d->ld < d->dim || d->ldo < d->dim || d->n_send < 0 || d->packed_bytes < 0 || d->nnz < 0)
+        return ADAQP_EINVAL;
+    if (d->overlap_begin < 0 || d->overlap_end < d->overlap_begin || d->dependent_begin < 0 ||
+        d->dependent_end < d->dependent_begin)
+        return ADAQP_EINVAL;
+    // the two row ranges are written concurrently: they must not intersect
+    if (d->overlap_begin < d->dependent_end && d->dependent_begin < d->overlap_end &&
+        d->overlap_end > d->overlap_begin && d->dependent_end > d->dependent_begin)
+        return ADAQP_EINVAL;
+    if (!d->feat_dev || !d->out_dev || !d->rowptr_dev) return ADAQP_EINVAL;
+    if (d->n_send > 0) {
+        if (!d->send_idx_dev || !d->bits_dev || !d->row_offset_dev || !d->packed_dev || !d->params_dev ||
+            !d->recv_packed_dev || !d->recv_params_dev)
+            return ADAQP_EINVAL;
+        if (d->direction == ADAQP_FORWARD && !d->halo_idx_dev) return ADAQP_EINVAL;
+    }
+    if (d->schedule != ADAQP_SERIAL) {
+        if (!d->event_fork || !d->event_join) return ADAQP_EINVAL;
+        if (d->stream_msg == d->stream_agg) return ADAQP_EINVAL;
+        // the two aggregations run at the same time: they need separate scratch
+        if (d->workspace_overlap_dev && d->workspace_overlap_dev == d->workspace_dependent_dev) return ADAQP_EINVAL;
+    }
+    return ADAQP_OK;
+}
+
+int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
+{
+    const int64_t rb = overlap_part ? d->overlap_begin : d->dependent_begin;
+    const int64_t re = overlap_part ? d->overlap_end : d->dependent_end;
+    const int64_t nz = overlap_part ? d->overlap_nnz : d->dependent_nnz;
+    void *ws = overlap_part ? d->workspace_overlap_dev : d->workspace_dependent_dev;
+    const int64_t wsb = overlap_part ? d->workspace_overlap_bytes : d->workspace_dependent_bytes;
+    return adaqp_spmm_csr(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, nz, d->feat_dev,
+                          d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, ws, wsb, st);
+}
+
+int loop_back(const adaqp_layer_desc *d, hipStream_t st)
+{
+    if (d->n_send == 0) return ADAQP_OK;
+    if (d->packed_bytes > 0)
+        ADAQP_HIP_TRY(hipMemcpyAsync(d->recv_packed_dev, d->packed_dev, (size_t)d->packed_bytes,
+                                     hipMemcpyDeviceToDevice, st));
+    ADAQP_HIP_TRY(hipMemcpyAsync(d->recv_params_dev, d->params_dev, (size_t)d->n_send * 2 * sizeof(float),
+                                 hipMemcpyDeviceToDevice, st));
+    return ADAQP_OK;
+}
+
+}  // namespace
+
+extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
+{
+    int rc = check_desc(d);
+    if (rc != ADAQP_OK) return rc;
+    // workspace sizes are checked up front so that a failure cannot leave the two streams half-joined
+    for (int part = 0; part < 2; ++part) {
+        const int64_t rows = part ? d->overlap_end - d->overlap_begin : d->dependent_end - d->dependent_begin;
+        int64_t nz = part ? d->overlap_nnz : d->dependent_nnz;
+        if (nz < 0 || nz > d->nnz) nz = d->nnz;
+        int64_t need = 0;
+        rc = adaqp_spmm_workspace_bytes(rows, nz, d->dim, &need);
+        if (rc != ADAQP_OK) return rc;
+        const int64_t have = part ? d->workspace_overlap_bytes : d->workspace_dependent_bytes;
+        const void *ws = part ? d->workspace_overlap_dev : d->workspace_dependent_dev;
+        if (rows > 0 && need > 0 && (!ws || have < need)) return ADAQP_ESIZE;
+    }
+
+    hipStream_t msg = (hipStream_t)d->stream_msg;
+    hipStream_t agg = d->schedule == ADAQP_SERIAL ? msg : (hipStream_t)d->stream_agg;
+    hipEvent_t fork = (hipEvent_t)d->event_fork, join = (hipEvent_t)d->event_join;
+    const bool forward = d->direction == ADAQP_FORWARD;
+    bool forked = false;
+    auto fork_now = [&]() -> int {
+        if (d->schedule == ADAQP_SERIAL) return ADAQP_OK;
+        ADAQP_HIP_TRY(hipEventRecord(fork, msg));
+        ADAQP_HIP_TRY(hipStreamWaitEvent(agg, fork, 0));
+        forked = true;
+        return ADAQP_OK;
+    };
+    auto join_now = [&]() -> int {
+        if (!forked) return ADAQP_OK;
+        ADAQP_HIP_TRY(hipEventRecord(join, agg));
+        ADAQP_HIP_TRY(hipStreamWaitEvent(msg, join, 0));
+        forked = false;
+        return ADAQP_OK;
+    };
+#define ADAQP_STEP(expr)                    \
+    do {                                    \
+        rc = (expr);                        \
+        if (rc != ADAQP_OK) { join_now(); return rc; } \
+    } while (0)
+
+    if (forward) {
+        // FREE: the central rows start right away.  ISOLATED: they start once quantisation is done.
+        if (d->schedule == ADAQP_FREE) {
+            ADAQP_STEP(fork_now());
+            ADAQP_STEP(aggregate(d, true, agg));
+        }
+        ADAQP_STEP(adaqp_quantize_pack(d->feat_dev, d->n_feat_rows, d->ld, d->dim, d->send_idx_dev, d->bits_dev,
+                                       d->row_offset_dev, d->n_send, d->seed, d->packed_dev, d->packed_bytes,
+                                       d->params_dev, msg));
+        if (d->schedule == ADAQP_ISOLATED) {
+            ADAQP_STEP(fork_now());
+            ADAQP_STEP(aggregate(d, true, agg));
+        }
+        ADAQP_STEP(loop_back(d, msg));
+        ADAQP_STEP(adaqp_unpack_dequant(d->recv_packed_dev, d->packed_bytes, d->recv_params_dev, d->bits_dev,
+                                        d->row_offset_dev, d->halo_idx_dev, d->n_send, d->dim, d->feat_dev,
+                                        d->n_feat_rows, d->ld, msg));
+        if (d->schedule == ADAQP_SERIAL) ADAQP_STEP(aggregate(d, true, msg));
+        ADAQP_STEP(aggregate(d, false, msg));
+    } else {
+        // backward: the rows that are sent are aggregated first, the local rows overlap their quantisation
+        // (FREE) or only their transfer (ISOLATED)
+        if (d->schedule == ADAQP_FREE) {
+            ADAQP_STEP(fork_now());
+            ADAQP_STEP(aggregate(d, true, agg));
+        }
+        ADAQP_STEP(aggregate(d, false, msg));
+        ADAQP_STEP(adaqp_quantize_pack(d->out_dev, d->dependent_end > d->overlap_end ? d->dependent_end : d->overlap_end,
+                                       d->ldo, d->dim, d->send_idx_dev, d->bits_dev, d->row_offset_dev, d->n_send,
+                                       d->seed, d->packed_dev, d->packed_bytes, d->params_dev, msg));
+        if (d->schedule == ADAQP_ISOLATED) {
+            ADAQP_STEP(fork_now());
+            ADAQP_STEP(aggregate(d, true, agg));
+        }
+        ADAQP_STEP(loop_back(d, msg));
+        if (d->schedule == ADAQP_SERIAL) ADAQP_STEP(aggregate(d, true, msg));
+    }
+    ADAQP_STEP(join_now());
+#undef ADAQP_STEP
+    return ADAQP_OK;
+}

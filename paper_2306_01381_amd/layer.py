@@ -1,0 +1,136 @@
+"""Device-resident state of one partition's layer step: uploads a partition, plans the buffer layout,
+allocates buffers / workspaces / streams / events with torch and HIP, and fills an adaqp_layer_desc.
+
+Everything computational happens inside libadaqp; this module only owns memory and handles.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .synth import Partition
+
+_hip: Optional[ctypes.CDLL] = None
+
+
+def _hip_runtime() -> ctypes.CDLL:
+    global _hip
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so")
+        _hip.hipEventCreateWithFlags.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint]
+        _hip.hipEventCreateWithFlags.restype = ctypes.c_int
+        _hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        _hip.hipEventDestroy.restype = ctypes.c_int
+    return _hip
+
+
+class HipEvent:
+    """A raw hipEvent_t (timing disabled) whose handle can be passed through the C ABI."""
+    _DISABLE_TIMING = 0x2
+
+    def __init__(self):
+        h = ctypes.c_void_p()
+        rc = _hip_runtime().hipEventCreateWithFlags(ctypes.byref(h), self._DISABLE_TIMING)
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreateWithFlags failed: {rc}")
+        self.handle = h.value
+
+    def __del__(self):
+        try:
+            if getattr(self, "handle", None):
+                _hip_runtime().hipEventDestroy(self.handle)
+        except Exception:
+            pass
+
+
+class SendPlan:
+    """Sorted slot order and byte offsets of one direction's messages (host arrays + device copies)."""
+
+    def __init__(self, dim: int, send_idx: np.ndarray, bits: np.ndarray, peer_of_slot: np.ndarray,
+                 n_peers: int, halo_idx: Optional[np.ndarray], device):
+        perm, off, pbp = B.adaqp_plan_layout(dim, bits, peer_of_slot, n_peers)
+        self.perm, self.row_offset_host, self.peer_byte_ptr = perm, off, pbp
+        self.send_idx_host = np.ascontiguousarray(send_idx[perm], dtype=np.int32)
+        self.bits_host = np.ascontiguousarray(bits[perm], dtype=np.uint8)
+        self.halo_idx_host = None if halo_idx is None or halo_idx.size == 0 else \
+            np.ascontiguousarray(halo_idx[perm], dtype=np.int32)
+        self.n = int(perm.shape[0])
+        self.packed_bytes = int(pbp[-1])
+        self.send_idx = torch.from_numpy(self.send_idx_host).to(device)
+        self.bits = torch.from_numpy(self.bits_host).to(device)
+        self.row_offset = torch.from_numpy(off).to(device)
+        self.halo_idx = None if self.halo_idx_host is None else torch.from_numpy(self.halo_idx_host).to(device)
+
+
+class LayerStep:
+    def __init__(self, p: Partition, device="cuda:0", seed: int = 0):
+        self.p = p
+        self.device = torch.device(device)
+        dev = self.device
+        cfg = p.cfg
+        self.dim = cfg.dim
+        self.backward = bool(cfg.backward)
+        self.seed = seed
+        self.rowptr = torch.from_numpy(p.rowptr).to(dev)
+        self.col = torch.from_numpy(p.col).to(dev)
+        self.val = torch.from_numpy(p.val).to(dev)
+        self.feat = torch.from_numpy(p.feat).to(dev)
+        self.out = torch.zeros((p.n_rows, cfg.dim), dtype=torch.float32, device=dev)
+        self.plan = SendPlan(cfg.dim, p.send_idx, p.bits, p.peer_of_slot, cfg.n_peers,
+                             None if self.backward else p.halo_idx, dev)
+        n = self.plan.n
+        nbytes = max(self.plan.packed_bytes, 4)
+        self.packed = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        self.params = torch.zeros((max(n, 1), 2), dtype=torch.float32, device=dev)
+        self.recv_packed = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        self.recv_params = torch.zeros((max(n, 1), 2), dtype=torch.float32, device=dev)
+        ob, oe = p.overlap_rows
+        db, de = p.dependent_rows
+        self.overlap_nnz = int(p.rowptr[oe] - p.rowptr[ob])
+        self.dependent_nnz = int(p.rowptr[de] - p.rowptr[db])
+        self.ws_overlap = torch.empty(max(B.adaqp_spmm_workspace_bytes(oe - ob, self.overlap_nnz, cfg.dim), 256),
+                                      dtype=torch.uint8, device=dev)
+        self.ws_dependent = torch.empty(max(B.adaqp_spmm_workspace_bytes(de - db, self.dependent_nnz, cfg.dim), 256),
+                                        dtype=torch.uint8, device=dev)
+        self.stream_msg = torch.cuda.Stream(device=dev)
+        self.stream_agg = torch.cuda.Stream(device=dev)
+        self.event_fork = HipEvent()
+        self.event_join = HipEvent()
+
+    def desc(self, schedule: int) -> B.LayerDesc:
+        p, pl = self.p, self.plan
+        d = B.LayerDesc()
+        d.direction = B.BACKWARD if self.backward else B.FORWARD
+        d.schedule = schedule
+        d.rowptr_dev, d.col_dev, d.val_dev = self.rowptr.data_ptr(), self.col.data_ptr(), self.val.data_ptr()
+        d.nnz = p.nnz
+        d.overlap_begin, d.overlap_end = p.overlap_rows
+        d.dependent_begin, d.dependent_end = p.dependent_rows
+        d.overlap_nnz, d.dependent_nnz = self.overlap_nnz, self.dependent_nnz
+        d.feat_dev, d.n_feat_rows, d.ld, d.dim = self.feat.data_ptr(), self.feat.shape[0], self.feat.stride(0), self.dim
+        d.out_dev, d.ldo = self.out.data_ptr(), self.out.stride(0)
+        d.send_idx_dev, d.bits_dev = pl.send_idx.data_ptr(), pl.bits.data_ptr()
+        d.row_offset_dev = pl.row_offset.data_ptr()
+        d.halo_idx_dev = None if pl.halo_idx is None else pl.halo_idx.data_ptr()
+        d.n_send, d.seed = pl.n, self.seed
+        d.packed_dev, d.params_dev = self.packed.data_ptr(), self.params.data_ptr()
+        d.recv_packed_dev, d.recv_params_dev = self.recv_packed.data_ptr(), self.recv_params.data_ptr()
+        d.packed_bytes = pl.packed_bytes
+        d.workspace_overlap_dev, d.workspace_overlap_bytes = self.ws_overlap.data_ptr(), self.ws_overlap.numel()
+        d.workspace_dependent_dev, d.workspace_dependent_bytes = self.ws_dependent.data_ptr(), self.ws_dependent.numel()
+        d.stream_msg = self.stream_msg.cuda_stream
+        d.stream_agg = self.stream_agg.cuda_stream
+        d.event_fork, d.event_join = self.event_fork.handle, self.event_join.handle
+        return d
+
+    def run(self, schedule: int = B.ISOLATED) -> None:
+        """Enqueues one layer step; synchronise stream_msg to wait for it."""
+        B.adaqp_layer_step(self.desc(schedule))
+
+    def synchronize(self) -> None:
+        self.stream_msg.synchronize()
+        self.stream_agg.synchronize()

@@ -1,0 +1,336 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: packed bytes, (Z, S) and de-quantised fp32 values bit-exact; aggregation within
+1e-5 * sum|terms| per output element (the fp64 oracle also returns that sum).
+"""
+import sys
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2306_01381_amd import binding as B                      # noqa: E402
+from paper_2306_01381_amd.layer import LayerStep, SendPlan          # noqa: E402
+from paper_2306_01381_amd.synth import CONFIGS, make_partition      # noqa: E402
+
+DEV = "cuda:0"
+SPMM_RTOL = 1e-5
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    B.lib()
+
+
+def _gpu_quantize(feat_np, dim, send_idx, bits, off, seed, packed_bytes, fill=0xAB):
+    feat = torch.from_numpy(feat_np).to(DEV)
+    packed = torch.full((max(packed_bytes, 4),), fill, dtype=torch.uint8, device=DEV)
+    params = torch.full((max(len(send_idx), 1), 2), float("nan"), dtype=torch.float32, device=DEV)
+    B.adaqp_quantize_pack(feat, dim, torch.from_numpy(send_idx).to(DEV), torch.from_numpy(bits).to(DEV),
+                          torch.from_numpy(off).to(DEV), seed, packed, params)
+    torch.cuda.synchronize()
+    return packed.cpu().numpy(), params.cpu().numpy()
+
+
+def _codec_case(oracle, feat_np, dim, send_idx, bits, peer, n_peers, seed, halo_rows=None):
+    """Quantise on both sides, compare bytes and params; de-quantise on both sides, compare floats."""
+    perm, off, pbp = oracle.plan_layout(dim, bits, peer, n_peers)
+    perm_g, off_g, pbp_g = B.adaqp_plan_layout(dim, bits, peer, n_peers)
+    assert np.array_equal(perm, perm_g) and np.array_equal(off, off_g) and np.array_equal(pbp, pbp_g)
+    s_idx = np.ascontiguousarray(send_idx[perm], dtype=np.int32)
+    s_bits = np.ascontiguousarray(bits[perm], dtype=np.uint8)
+    nbytes = int(pbp[-1])
+    want_packed, want_params, _ = oracle.quantize_pack(feat_np, dim, s_idx, s_bits, off, seed, nbytes)
+    got_packed, got_params = _gpu_quantize(feat_np, dim, s_idx, s_bits, off, seed, nbytes)
+    n = len(s_idx)
+    assert np.array_equal(got_params[:n].view(np.uint32), want_params.view(np.uint32)), "(Z, S) differ"
+    if nbytes:
+        bad = np.nonzero(got_packed[:nbytes] != want_packed)[0]
+        assert bad.size == 0, f"{bad.size} packed bytes differ, first at {bad[:5]}"
+    # receive side, into a copy with a sentinel so that stray writes show
+    ld = feat_np.shape[1]
+    n_rows = feat_np.shape[0]
+    halo = np.ascontiguousarray(halo_rows if halo_rows is not None
+                                else np.random.default_rng(seed).permutation(n_rows)[:n], dtype=np.int32)
+    want = np.full((n_rows, ld), np.float32(-123.5))
+    oracle.unpack_dequant(want_packed, want_params, s_bits, off, halo, dim, want)
+    got = torch.full((n_rows, ld), -123.5, dtype=torch.float32, device=DEV)
+    B.adaqp_unpack_dequant(torch.from_numpy(want_packed if nbytes else np.zeros(4, np.uint8)).to(DEV),
+                           torch.from_numpy(want_params if n else np.zeros((1, 2), np.float32)).to(DEV),
+                           torch.from_numpy(s_bits).to(DEV), torch.from_numpy(off).to(DEV),
+                           torch.from_numpy(halo).to(DEV), dim, got)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32)), "de-quantised rows differ"
+
+
+@pytest.mark.parametrize("dim,ld", [(128, 128), (602, 602), (256, 256), (300, 300), (300, 301), (7, 7), (1, 1),
+                                    (8, 12), (9, 9), (33, 40), (63, 63), (64, 64), (65, 66), (1000, 1000),
+                                    (4096, 4096), (4100, 4100), (5000, 5001)])
+def test_codec_shapes(oracle, dim, ld):
+    _say(f"codec dim={dim} ld={ld}")
+    rng = np.random.default_rng(dim * 7 + ld)
+    n_rows, n = 300, 211                       # several blocks of rows and a ragged last block
+    feat = rng.standard_normal((n_rows, ld), dtype=np.float32)
+    feat[3] = 1.25                                                    # constant row
+    feat[4, : dim // 2] = 0.0
+    feat[5] = np.maximum(feat[5], 0)
+    feat[6] *= np.float32(1e-3)
+    send = rng.integers(0, n_rows, size=n).astype(np.int32)
+    send[:8] = np.arange(8)
+    bits = rng.choice(np.array([2, 4, 8], dtype=np.uint8), size=n)
+    peer = np.sort(rng.integers(0, 3, size=n)).astype(np.int32)
+    _codec_case(oracle, feat, dim, send, bits, peer, 3, seed=dim)
+
+
+@pytest.mark.parametrize("b", [2, 4, 8])
+def test_codec_single_width_and_seeds(oracle, b):
+    _say(f"codec single width b={b}")
+    rng = np.random.default_rng(b)
+    feat = rng.standard_normal((64, 602), dtype=np.float32)
+    for seed in (0, 1, 2**32 + 5, 2**64 - 1):
+        _codec_case(oracle, feat, 602, np.arange(64, dtype=np.int32), np.full(64, b, np.uint8),
+                    np.zeros(64, np.int32), 1, seed)
+
+
+def test_codec_c0(oracle):
+    _say("codec c0")
+    p = make_partition(CONFIGS["c0"])
+    _codec_case(oracle, p.feat, p.cfg.dim, p.send_idx, p.bits, p.peer_of_slot, p.cfg.n_peers, seed=0,
+                halo_rows=None)
+
+
+def test_codec_distributions(oracle):
+    """The value distributions of the four workloads at reduced row counts."""
+    for name in ("c1", "c2", "c3", "c4"):
+        _say(f"codec distribution {name}")
+        cfg = replace(CONFIGS[name], n_local=3000, n_halo=2500, n_send=1500, mean_degree=6.0)
+        p = make_partition(cfg)
+        feat = p.feat if not cfg.backward else np.concatenate([p.feat, p.feat[:1600] * 3], 0)
+        send = p.send_idx if not cfg.backward else (p.send_idx % feat.shape[0]).astype(np.int32)
+        _codec_case(oracle, np.ascontiguousarray(feat), cfg.dim, send, p.bits, p.peer_of_slot, cfg.n_peers, seed=11)
+
+
+def test_codec_skips_invalid_slots_and_empty_input(oracle):
+    _say("codec invalid slots")
+    rng = np.random.default_rng(0)
+    dim = 40
+    feat = rng.standard_normal((10, dim), dtype=np.float32)
+    send = np.array([0, 99, 2, -1, 4], dtype=np.int32)              # 99 and -1 are out of range
+    bits = np.array([2, 2, 3, 4, 8], dtype=np.uint8)                # 3 is not a width
+    off = np.array([0, 12, 24, 48, 68], dtype=np.int64)
+    nbytes = 68 + 40
+    got_packed, got_params = _gpu_quantize(feat, dim, send, bits, off, 1, nbytes, fill=0xCD)
+    # the oracle rejects invalid slots outright and keys the random stream by position: give it valid
+    # stand-ins at the skipped positions and compare only the bytes of the valid slots
+    send_v, bits_v = send.copy(), bits.copy()
+    send_v[[1, 3]] = 0
+    bits_v[2] = 4
+    full_packed, full_params, _ = oracle.quantize_pack(feat, dim, send_v, bits_v, off, 1, nbytes)
+    assert np.array_equal(got_packed[0:12], full_packed[0:12])
+    assert np.array_equal(got_packed[68:108], full_packed[68:108])
+    assert np.all(got_packed[12:68] == 0xCD)                          # skipped slots wrote nothing
+    assert np.array_equal(got_params[[0, 4]].view(np.uint32), full_params[[0, 4]].view(np.uint32))
+    assert np.isnan(got_params[[1, 2, 3]]).all()
+    # a row that would overrun the buffer is skipped too
+    got_packed, got_params = _gpu_quantize(feat, dim, send[:1], np.array([8], np.uint8), np.array([80], np.int64),
+                                           1, 100, fill=0xCD)
+    assert np.all(got_packed == 0xCD) and np.isnan(got_params[0]).all()
+    # empty input
+    e32, e8, e64 = np.zeros(0, np.int32), np.zeros(0, np.uint8), np.zeros(0, np.int64)
+    got_packed, _ = _gpu_quantize(feat, dim, e32, e8, e64, 1, 0, fill=0xCD)
+    assert np.all(got_packed == 0xCD)
+
+
+# ------------------------------------------------------------------------------------------------------
+# aggregation
+# ------------------------------------------------------------------------------------------------------
+
+def _gpu_spmm(rowptr, col, val, rb, re, H, dim, nnz_range=-1, out_fill=7.0, ldo=None):
+    n_rows_total = rowptr.shape[0] - 1
+    ldo = dim if ldo is None else ldo
+    out = torch.full((n_rows_total, ldo), out_fill, dtype=torch.float32, device=DEV)
+    nz = int(rowptr[re] - rowptr[rb]) if nnz_range == "exact" else -1
+    ws_bytes = B.adaqp_spmm_workspace_bytes(re - rb, nz if nz >= 0 else len(col), dim)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
+    colt = torch.from_numpy(col).to(DEV) if len(col) else torch.zeros(1, dtype=torch.int32, device=DEV)[:0]
+    valt = torch.from_numpy(val).to(DEV) if len(val) else torch.zeros(1, dtype=torch.float32, device=DEV)[:0]
+    B.adaqp_spmm_csr(torch.from_numpy(rowptr).to(DEV), colt, valt, rb, re, torch.from_numpy(H).to(DEV), dim, out,
+                     ws, nnz_range=nz)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _check_spmm(oracle, rowptr, col, val, rb, re, H, dim, **kw):
+    got = _gpu_spmm(rowptr, col, val, rb, re, H, dim, **kw)
+    want, mag = oracle.spmm_csr(rowptr, col, val, rb, re, H, dim)
+    err = np.abs(got[rb:re, :dim].astype(np.float64) - want)
+    tol = SPMM_RTOL * mag + 1e-30
+    worst = float((err / tol).max()) if err.size else 0.0
+    assert worst <= 1.0, f"worst error {worst:.3f} x tolerance"
+    assert np.all(got[:rb] == 7.0) and np.all(got[re:] == 7.0), "rows outside the range were written"
+    if got.shape[1] > dim:
+        assert np.all(got[:, dim:] == 7.0), "columns past dim were written"
+    return got
+
+
+def _random_graph(rng, n_rows, n_cols, degs):
+    rowptr = np.zeros(n_rows + 1, dtype=np.int64)
+    cols = []
+    for r in range(n_rows):
+        d = int(min(degs[r], n_cols))
+        c = np.sort(rng.choice(n_cols, size=d, replace=False)) if d else np.zeros(0, np.int64)
+        cols.append(c)
+        rowptr[r + 1] = rowptr[r] + d
+    col = np.concatenate(cols).astype(np.int32) if cols else np.zeros(0, np.int32)
+    val = rng.standard_normal(col.shape[0]).astype(np.float32)
+    return rowptr, col, val
+
+
+@pytest.mark.parametrize("dim,ldh", [(128, 128), (602, 602), (256, 256), (300, 300), (1, 1), (7, 9), (66, 66),
+                                     (130, 132), (2048, 2048), (2052, 2052), (515, 515)])
+def test_spmm_shapes(oracle, dim, ldh):
+    _say(f"spmm dim={dim} ldh={ldh}")
+    rng = np.random.default_rng(dim)
+    n_rows, n_cols = 700, 900
+    degs = rng.integers(0, 12, size=n_rows)
+    degs[10] = 800                                                     # a row far longer than one piece
+    degs[11] = 0
+    degs[500:520] = 0                                                  # a run of empty rows
+    degs[699] = 300                                                    # heavy last row
+    rowptr, col, val = _random_graph(rng, n_rows, n_cols, degs)
+    H = np.zeros((n_cols, ldh), dtype=np.float32)
+    H[:, :dim] = rng.standard_normal((n_cols, dim), dtype=np.float32)
+    _check_spmm(oracle, rowptr, col, val, 0, n_rows, H, dim)
+    _check_spmm(oracle, rowptr, col, val, 9, 12, H, dim, nnz_range="exact")
+    _check_spmm(oracle, rowptr, col, val, 495, 700, H, dim, nnz_range="exact")
+
+
+def test_spmm_degenerate(oracle):
+    _say("spmm degenerate")
+    rng = np.random.default_rng(1)
+    H = rng.standard_normal((5, 16), dtype=np.float32)
+    # all rows empty
+    rowptr = np.zeros(41, dtype=np.int64)
+    got = _check_spmm(oracle, rowptr, np.zeros(0, np.int32), np.zeros(0, np.float32), 0, 40, H, 16)
+    assert np.all(got == 0)
+    # a single row holding everything
+    rowptr = np.array([0, 5], dtype=np.int64)
+    _check_spmm(oracle, rowptr, np.arange(5, dtype=np.int32), np.ones(5, np.float32), 0, 1, H, 16)
+    # one very long row between empty ones (more entries than any piece)
+    n = 5000
+    Hbig = rng.standard_normal((n, 64), dtype=np.float32)
+    rowptr = np.array([0, 0, 0, n, n, n], dtype=np.int64)
+    _check_spmm(oracle, rowptr, np.arange(n, dtype=np.int32), rng.standard_normal(n).astype(np.float32), 0, 5,
+                Hbig, 64)
+    # out-of-range columns are skipped, not read
+    rowptr = np.array([0, 3], dtype=np.int64)
+    col = np.array([0, 77, 2], dtype=np.int32)
+    val = np.array([1.0, 5.0, 2.0], dtype=np.float32)
+    got = _gpu_spmm(rowptr, col, val, 0, 1, H, 16)
+    assert np.allclose(got[0], H[0] + 2 * H[2], rtol=1e-6)
+    # empty range
+    got = _gpu_spmm(np.array([0, 3], dtype=np.int64), col, val, 1, 1, H, 16)
+    assert np.all(got == 7.0)
+
+
+def test_spmm_is_deterministic(oracle):
+    _say("spmm determinism")
+    p = make_partition(CONFIGS["c0"])
+    a = _gpu_spmm(p.rowptr, p.col, p.val, 0, p.n_rows, p.feat, p.cfg.dim)
+    b = _gpu_spmm(p.rowptr, p.col, p.val, 0, p.n_rows, p.feat, p.cfg.dim)
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+def test_spmm_c0_and_nonnegative_long_rows(oracle):
+    _say("spmm c0")
+    p = make_partition(CONFIGS["c0"])
+    _check_spmm(oracle, p.rowptr, p.col, p.val, 0, p.n_rows, p.feat, p.cfg.dim)
+    _check_spmm(oracle, p.rowptr, p.col, p.val, 0, p.n_central, p.feat, p.cfg.dim, nnz_range="exact")
+    _check_spmm(oracle, p.rowptr, p.col, p.val, p.n_central, p.n_rows, p.feat, p.cfg.dim, nnz_range="exact")
+    # non-negative features and weights: partial sums grow monotonically, the hardest case for fp32 sums
+    rng = np.random.default_rng(2)
+    n_cols = 30000
+    degs = np.array([25000, 3, 12000, 1])
+    rowptr, col, val = _random_graph(rng, 4, n_cols, degs)
+    val = np.abs(val)
+    H = np.abs(rng.standard_normal((n_cols, 256), dtype=np.float32))
+    _check_spmm(oracle, rowptr, col, val, 0, 4, H, 256)
+
+
+# ------------------------------------------------------------------------------------------------------
+# the layer step
+# ------------------------------------------------------------------------------------------------------
+
+def _oracle_layer(oracle, p, seed):
+    """Composes the oracle's pieces in the order of Sec. 3.1: quantise, exchange (identity), de-quantise,
+    aggregate.  Returns (packed, params, feat_after, out64, mag64)."""
+    cfg = p.cfg
+    perm, off, pbp = oracle.plan_layout(cfg.dim, p.bits, p.peer_of_slot, cfg.n_peers)
+    s_idx = np.ascontiguousarray(p.send_idx[perm])
+    s_bits = np.ascontiguousarray(p.bits[perm])
+    if not cfg.backward:
+        packed, params, _ = oracle.quantize_pack(p.feat, cfg.dim, s_idx, s_bits, off, seed, int(pbp[-1]))
+        feat = p.feat.copy()
+        oracle.unpack_dequant(packed, params, s_bits, off, np.ascontiguousarray(p.halo_idx[perm]), cfg.dim, feat)
+        out64, mag = oracle.spmm_csr(p.rowptr, p.col, p.val, 0, p.n_rows, feat, cfg.dim)
+        return packed, params, feat, out64, mag
+    out = np.zeros((p.n_rows, cfg.dim), dtype=np.float32)
+    out64, mag = oracle.spmm_csr(p.rowptr, p.col, p.val, 0, p.n_rows, p.feat, cfg.dim, out=out)
+    return None, None, None, out64, mag
+
+
+@pytest.mark.parametrize("name", ["c0", "c0_backward"])
+def test_layer_step_matches_oracle_in_every_schedule(oracle, name):
+    _say(f"layer step {name}")
+    if name == "c0":
+        p = make_partition(CONFIGS["c0"])
+    else:
+        p = make_partition(replace(CONFIGS["c4"], n_local=2000, n_halo=1800, n_send=1500, mean_degree=9.0, dim=128))
+    cfg = p.cfg
+    seed = 1234
+    packed_w, params_w, feat_w, out64, mag = _oracle_layer(oracle, p, seed)
+    results = []
+    for schedule in (B.SERIAL, B.ISOLATED, B.FREE):
+        L = LayerStep(p, DEV, seed=seed)
+        if not cfg.backward:
+            # poison what the step must produce, so that a missing dependency shows as NaN
+            L.feat[cfg.n_local: cfg.n_local + cfg.n_send] = float("nan")
+        L.out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        L.run(schedule)
+        L.synchronize()
+        out = L.out.cpu().numpy()
+        err = np.abs(out.astype(np.float64) - out64)
+        assert np.all(err <= SPMM_RTOL * mag + 1e-30), f"schedule {schedule}: aggregation off"
+        packed = L.recv_packed.cpu().numpy()[: L.plan.packed_bytes]
+        params = L.recv_params.cpu().numpy()[: L.plan.n]
+        if not cfg.backward:
+            assert np.array_equal(packed, packed_w)
+            assert np.array_equal(params.view(np.uint32), params_w.view(np.uint32))
+            assert np.array_equal(L.feat.cpu().numpy().view(np.uint32), feat_w.view(np.uint32))
+        results.append((out, packed, params))
+    for out, packed, params in results[1:]:
+        assert np.array_equal(out.view(np.uint32), results[0][0].view(np.uint32)), "schedules disagree"
+        assert np.array_equal(packed, results[0][1]) and np.array_equal(params.view(np.uint32),
+                                                                        results[0][2].view(np.uint32))
+    if cfg.backward:
+        # the oracle quantises the GPU's own fp32 aggregate: the codes depend on every bit of the input, and
+        # the aggregate is only specified to a tolerance
+        L = LayerStep(p, DEV, seed=seed)
+        L.run(B.SERIAL)
+        L.synchronize()
+        g = L.out.cpu().numpy()
+        want_packed, want_params, _ = oracle.quantize_pack(g, cfg.dim, L.plan.send_idx_host, L.plan.bits_host,
+                                                           L.plan.row_offset_host, seed, L.plan.packed_bytes)
+        assert np.array_equal(L.recv_packed.cpu().numpy()[: L.plan.packed_bytes], want_packed)
+        assert np.array_equal(L.recv_params.cpu().numpy()[: L.plan.n].view(np.uint32), want_params.view(np.uint32))

@@ -1,0 +1,94 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its host logic
+(layout planning, argument validation that happens before any launch) behaves as the header says."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2306_01381_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "adaqp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adaqp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = _declared_symbols()
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(B.EXPORTS)
+    assert B.adaqp_version() >= 100
+    assert L.adaqp_strerror(B.ESIZE).decode().startswith("buffer")
+
+
+def test_row_stride():
+    assert B.adaqp_row_stride(602, 2) == 152 and B.adaqp_row_stride(602, 4) == 304
+    assert B.adaqp_row_stride(602, 8) == 604 and B.adaqp_row_stride(1, 2) == 4
+    assert B.adaqp_row_stride(256, 2) == 64
+    assert B.adaqp_row_stride(0, 2) == -1 and B.adaqp_row_stride(8, 3) == -1
+
+
+def test_plan_layout_matches_oracle(oracle):
+    rng = np.random.default_rng(4)
+    for dim in (1, 5, 128, 300, 602, 4100):
+        for n, n_peers in ((0, 2), (1, 1), (37, 3), (500, 7)):
+            peer = np.sort(rng.integers(0, n_peers, size=n)).astype(np.int32)
+            bits = rng.choice(np.array([2, 4, 8], dtype=np.uint8), size=n)
+            got = B.adaqp_plan_layout(dim, bits, peer, n_peers)
+            want = oracle.plan_layout(dim, bits, peer, n_peers)
+            for g, w in zip(got, want):
+                assert np.array_equal(g, w)
+
+
+def test_plan_layout_errors():
+    with pytest.raises(B.AdaqpError) as e:
+        B.adaqp_plan_layout(8, np.array([2, 5], np.uint8), np.array([0, 0], np.int32), 1)
+    assert e.value.status == B.EBITS
+    with pytest.raises(B.AdaqpError) as e:
+        B.adaqp_plan_layout(8, np.array([2, 2], np.uint8), np.array([1, 0], np.int32), 2)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_plan_layout(0, np.array([2], np.uint8), np.array([0], np.int32), 1)
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_plan_layout(8, np.array([2], np.uint8), np.array([3], np.int32), 3)
+
+
+def test_argument_errors_are_caught_before_any_launch():
+    L = B.lib()
+    one = ctypes.c_void_p(256)          # a non-NULL, aligned dummy; never dereferenced on these paths
+    # zero counts are successful no-ops
+    assert L.adaqp_quantize_pack(None, 0, 8, 8, None, None, None, 0, 0, None, 0, None, None) == B.OK
+    assert L.adaqp_unpack_dequant(None, 0, None, None, None, None, 0, 8, None, 0, 8, None) == B.OK
+    assert L.adaqp_spmm_csr(None, None, None, 0, 3, 3, -1, None, 0, 8, 8, None, 8, None, 0, None) == B.OK
+    # bad shapes
+    assert L.adaqp_quantize_pack(one, 4, 7, 8, one, one, one, 1, 0, one, 64, one, None) == B.EINVAL   # ld < dim
+    assert L.adaqp_quantize_pack(one, 4, 8, 0, one, one, one, 1, 0, one, 64, one, None) == B.EINVAL   # dim 0
+    assert L.adaqp_quantize_pack(one, 4, 8, 8, one, one, one, -1, 0, one, 64, one, None) == B.EINVAL  # n < 0
+    assert L.adaqp_quantize_pack(None, 4, 8, 8, one, one, one, 1, 0, one, 64, one, None) == B.EINVAL  # NULL
+    assert L.adaqp_unpack_dequant(one, 64, one, one, one, one, 1, 8, None, 4, 8, None) == B.EINVAL
+    assert L.adaqp_unpack_dequant(one, 64, one, one, one, one, 1, 8, one, 4, 4, None) == B.EINVAL     # ld < dim
+    assert L.adaqp_spmm_csr(one, one, one, 5, 2, 1, -1, one, 4, 8, 8, one, 8, one, 1 << 20, None) == B.EINVAL
+    assert L.adaqp_spmm_csr(one, one, one, 5, 0, 2, -1, one, 4, 4, 8, one, 8, one, 1 << 20, None) == B.EINVAL
+    # workspace too small
+    assert L.adaqp_spmm_csr(one, one, one, 5, 0, 2, -1, one, 4, 8, 8, one, 8, one, 16, None) == B.ESIZE
+    assert L.adaqp_layer_step(None) == B.EINVAL
+    d = B.LayerDesc()
+    d.direction = 7
+    assert L.adaqp_layer_step(ctypes.byref(d)) == B.EINVAL
+
+
+def test_workspace_query():
+    assert B.adaqp_spmm_workspace_bytes(0, 0, 8) == 0
+    small = B.adaqp_spmm_workspace_bytes(2000, 20000, 128)
+    big = B.adaqp_spmm_workspace_bytes(58000, 28_000_000, 602)
+    assert small % 256 == 0 and big % 256 == 0 and 0 < small < big < (1 << 30)
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_spmm_workspace_bytes(-1, 0, 8)
