@@ -5,13 +5,17 @@
 // side does the reverse.  Nothing is a dense contraction, so the matrix cores are not used.
 //
 // Send side, one pass over memory.  A row of dim floats is cut into "granules" of 8 consecutive columns;
-// a granule is the unit of everything: 32 bytes of input (two 16-byte loads), one Philox4x32-10 call (its
-// 128 bits are the eight 16-bit rounding values), b bytes of output.  A row is owned by LPR = 2^k lanes of
-// a wave, lane l holding granules l, l + LPR, l + 2*LPR, ... (GPL of them) in registers, so that at each
-// step the LPR lanes of a row read LPR*32 contiguous bytes.  min / max are reduced over the row's lanes
-// with xor shuffles, the row's (Z, S, inv) are computed redundantly by every lane, and the codes are packed
-// in registers.  LPR and GPL are chosen on the host so that LPR*GPL barely exceeds dim/8 (D=602: 16 x 5,
-// D=256: 8 x 4, D=300: 8 x 5, D=128: 4 x 4); a wave therefore carries 64/LPR rows.
+// a granule is the unit of everything: 32 bytes of input, one Philox4x32-10 call (its 128 bits are the
+// eight 16-bit rounding values), b bytes of output.  A row is owned by LPR = 2^k lanes of a wave, lane l
+// holding granules l, l + LPR, l + 2*LPR, ... (GPL of them) in registers, so that at each step the LPR
+// lanes of a row read LPR*32 contiguous bytes.  LPR and GPL are chosen on the host so that LPR*GPL barely
+// exceeds dim/8 (D=602: 16 x 5, D=256: 8 x 4, D=300: 8 x 5, D=128: 4 x 4); a wave carries 64/LPR rows.
+// Order of work inside a wave: (1) issue the loads of the slot's index entries; (2) while they are in
+// flight, run Philox for all GPL granules - the random values depend only on (seed, slot, column), not on
+// memory; (3) issue all row loads; (4) min / max in registers, xor-shuffle reduction over the row's lanes,
+// (Z, S, inv) computed redundantly by every lane; (5) codes, packed in registers, stored.
+// 32-bit integer multiplies issue at full rate on gfx950 (measured), so a Philox call costs about 60 VALU
+// issue slots per lane, the rest of a granule about as much again.
 //
 // fp32 arithmetic is written operation by operation and the file is compiled with -ffp-contract=off: the
 // integer codes depend on every rounding.
@@ -32,12 +36,12 @@ __device__ __forceinline__ Rand128 philox4x32_10(uint32_t c0, uint32_t c1, uint3
     constexpr uint32_t kWeylA = 0x9E3779B9u, kWeylB = 0xBB67AE85u;
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        const uint32_t hiA = __umulhi(kMulA, c0), loA = kMulA * c0;
-        const uint32_t hiB = __umulhi(kMulB, c2), loB = kMulB * c2;
-        c0 = hiB ^ c1 ^ k0;
-        c1 = loB;
-        c2 = hiA ^ c3 ^ k1;
-        c3 = loA;
+        const uint64_t pA = (uint64_t)kMulA * c0;            // one v_mad_u64_u32 each
+        const uint64_t pB = (uint64_t)kMulB * c2;
+        c0 = (uint32_t)(pB >> 32) ^ c1 ^ k0;
+        c1 = (uint32_t)pB;
+        c2 = (uint32_t)(pA >> 32) ^ c3 ^ k1;
+        c3 = (uint32_t)pA;
         k0 += kWeylA;
         k1 += kWeylB;
     }
@@ -45,6 +49,13 @@ __device__ __forceinline__ Rand128 philox4x32_10(uint32_t c0, uint32_t c1, uint3
 }
 
 constexpr uint32_t kCounterTag = 0x41645150u;
+
+// Pins a value to this point of the program: the optimiser may neither sink its computation below nor
+// rematerialise it later.
+__device__ __forceinline__ void pin(Rand128 &r)
+{
+    asm volatile("" : "+v"(r.w0), "+v"(r.w1), "+v"(r.w2), "+v"(r.w3));
+}
 
 struct QuantArgs {
     const float *feat;
@@ -86,8 +97,11 @@ __device__ __forceinline__ void store_vec(float *p, const float *src)
 }
 
 // Codes of one granule (8 columns) at width B, merged little-endian into lo (and hi for B == 8).
-template <int B>
-__device__ __forceinline__ void quantise_granule(const float (&x)[8], float Z, float inv, float levels,
+// inv16 = inv * 2^16 and levels16 = (2^B - 1) * 2^16: scaling by a power of two commutes with fp32 rounding,
+// so trunc(min((x - Z) * inv, L) * 2^16) == trunc(min((x - Z) * inv16, levels16)) whenever inv16 is finite.
+// MASK: zero the codes of columns >= dim (only the last granule step of a row can need it).
+template <int B, bool MASK>
+__device__ __forceinline__ void quantise_granule(const float (&x)[8], float Z, float inv16, float levels16,
                                                  const Rand128 &rnd, int32_t col0, int32_t dim,
                                                  uint32_t &lo, uint32_t &hi)
 {
@@ -96,12 +110,12 @@ __device__ __forceinline__ void quantise_granule(const float (&x)[8], float Z, f
     hi = 0u;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-        float pos = (x[k] - Z) * inv;                         // Eq. 4 argument, >= 0
-        pos = fminf(pos, levels);                             // the top element may overshoot by an ulp
-        const uint32_t fixed = (uint32_t)(pos * 65536.0f);    // 16.16 fixed point, truncated
+        float pos = (x[k] - Z) * inv16;                       // Eq. 4 argument in 16.16 fixed point, >= 0
+        pos = fminf(pos, levels16);                           // the top element may overshoot by an ulp
+        const uint32_t fixed = (uint32_t)pos;                 // truncated
         const uint32_t r16 = (k & 1) ? (words[k >> 1] >> 16) : (words[k >> 1] & 0xFFFFu);
         uint32_t code = (fixed + r16) >> 16;                  // App. A.1: up with probability frac
-        code = (col0 + k < dim) ? code : 0u;                  // padding bits are zero
+        if (MASK) code = (col0 + k < dim) ? code : 0u;        // padding bits are zero
         if (B * k < 32) lo |= code << ((B * k) & 31);
         else            hi |= code << ((B * k) & 31);
     }
@@ -125,7 +139,7 @@ __device__ __forceinline__ void store_granule(uint8_t *row, int32_t g, int32_t n
     }
 }
 
-struct RowScale { float Z, S, inv; };
+struct RowScale { float Z, S, inv16; };
 
 __device__ __forceinline__ RowScale row_scale(float mn, float mx, float levels)
 {
@@ -133,12 +147,28 @@ __device__ __forceinline__ RowScale row_scale(float mn, float mx, float levels)
     rs.Z = mn + 0.0f;                     // -0 -> +0, so that any reduction order gives the same zero-point
     const float range = (mx + 0.0f) - rs.Z;
     rs.S = 0.0f;
-    rs.inv = 0.0f;
+    rs.inv16 = 0.0f;
     if (range > 0.0f) {
         rs.S = range / levels;            // Eq. 4 scale, correctly rounded fp32 division
-        rs.inv = levels / range;
+        rs.inv16 = (levels / range) * 65536.0f;
     }
     return rs;
+}
+
+template <int B, int GPL>
+__device__ __forceinline__ void quantise_row(const float (&x)[GPL][8], const Rand128 (&rnd)[GPL],
+                                             const RowScale &rs, int lpr, int l, int32_t dim, int32_t n_granules,
+                                             uint8_t *row, int64_t stride, bool valid)
+{
+    const float levels16 = (float)((1 << B) - 1) * 65536.0f;
+#pragma unroll
+    for (int i = 0; i < GPL; ++i) {
+        const int32_t g = i * lpr + l;
+        uint32_t lo, hi;
+        if (i < GPL - 1) quantise_granule<B, false>(x[i], rs.Z, rs.inv16, levels16, rnd[i], g * 8, dim, lo, hi);
+        else             quantise_granule<B, true>(x[i], rs.Z, rs.inv16, levels16, rnd[i], g * 8, dim, lo, hi);
+        if (valid && g < n_granules) store_granule<B>(row, g, n_granules, stride, lo, hi);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -154,39 +184,54 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
     const int64_t s = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * rows_per_wave + (lane >> a.lpr_log2);
     const int l = lane & (lpr - 1);
 
-    bool active = s < a.n_send;
-    int32_t r = 0, b = 0;
-    int64_t off = 0;
-    if (active) {
-        r = a.send_idx[s];
-        b = a.bits[s];
-        off = a.row_offset[s];
-    }
-    const int64_t stride = 4 * (((int64_t)a.dim * b + 31) >> 5);
-    active = active && r >= 0 && r < a.n_feat_rows && (b == 2 || b == 4 || b == 8) && off >= 0 &&
-             (off & 3) == 0 && off + stride <= a.packed_bytes;
-    const float *h = a.feat + (active ? (int64_t)r * a.ld : 0);
+    // (1) the slot's index entries
+    const bool in_range = s < a.n_send;
+    const int64_t s_safe = in_range ? s : 0;
+    const int32_t r_raw = a.send_idx[s_safe];
+    const int32_t b = a.bits[s_safe];
+    const int64_t off = a.row_offset[s_safe];
 
-    // gather: the row's granules l, l+LPR, ... into registers; columns past dim repeat the first element,
-    // which leaves min and max alone
+    // (2) rounding values of the lane's granules.  They depend on (seed, slot, column) only, not on memory:
+    // the first kEarly calls run while the index entries are in flight, the rest after the row loads have
+    // been issued (the scheduling barriers keep the compiler from sinking them behind the loads' wait).
+    constexpr int kEarly = GPL < 2 ? GPL : 2;
+    Rand128 rnd[GPL];
+    const uint32_t s_lo = (uint32_t)s, s_hi = (uint32_t)((uint64_t)s >> 32);
+#pragma unroll
+    for (int i = 0; i < kEarly; ++i) {
+        rnd[i] = philox4x32_10((uint32_t)(i * lpr + l), s_lo, s_hi, kCounterTag, a.seed_lo, a.seed_hi);
+        pin(rnd[i]);
+    }
+
+    const int64_t stride = 4 * (((int64_t)a.dim * b + 31) >> 5);
+    const bool valid = in_range && r_raw >= 0 && r_raw < a.n_feat_rows && (b == 2 || b == 4 || b == 8) &&
+                       off >= 0 && (off & 3) == 0 && off + stride <= a.packed_bytes;
+    // lanes without a valid slot read row 0 and store nothing: every load below is unconditional
+    const float *h = a.feat + (valid ? (int64_t)r_raw * a.ld : 0);
+
+    // (3) gather the lane's granules.  Only the last step can reach past the row; there the column is clamped
+    // to the row's last vector, which repeats real elements and so leaves min and max alone.
     float x[GPL][8];
-    const float first = active ? h[0] : 0.0f;
 #pragma unroll
     for (int i = 0; i < GPL; ++i) {
         const int32_t c0 = (i * lpr + l) * 8;
 #pragma unroll
         for (int v = 0; v < 8 / VW; ++v) {
-            const int32_t c = c0 + v * VW;
-            if (active && c < a.dim) {
-                load_vec<VW>(h + c, &x[i][v * VW]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < VW; ++k) x[i][v * VW + k] = first;
-            }
+            int32_t c = c0 + v * VW;
+            if (i == GPL - 1) c = c < a.dim - VW ? c : a.dim - VW;
+            load_vec<VW>(h + c, &x[i][v * VW]);
         }
     }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = kEarly; i < GPL; ++i) {
+        rnd[i] = philox4x32_10((uint32_t)(i * lpr + l), s_lo, s_hi, kCounterTag, a.seed_lo, a.seed_hi);
+        pin(rnd[i]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 
-    float mn = first, mx = first;
+    // (4) row minimum / maximum
+    float mn = x[0][0], mx = x[0][0];
 #pragma unroll
     for (int i = 0; i < GPL; ++i)
 #pragma unroll
@@ -198,31 +243,25 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
         mn = fminf(mn, __shfl_xor(mn, m, kWave));
         mx = fmaxf(mx, __shfl_xor(mx, m, kWave));
     }
-    if (!active) return;                                   // no cross-lane operation below this line
+    const uint64_t valid_mask = __ballot(valid);
+    if (valid_mask == 0) return;
+    const int32_t b_first = __builtin_amdgcn_readlane(b, __ffsll((long long)valid_mask) - 1);
+    const bool one_width = __ballot(valid && b != b_first) == 0;       // no cross-lane operation below this line
 
-    const float levels = (float)((1 << b) - 1);
+    const float levels = (float)((1 << (b & 15)) - 1);
     const RowScale rs = row_scale(mn, mx, levels);
-    if (l == 0) *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
+    if (valid && l == 0) *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
 
-    uint8_t *row = a.packed + off;
-    const uint32_t s_lo = (uint32_t)s, s_hi = (uint32_t)((uint64_t)s >> 32);
-#pragma unroll
-    for (int i = 0; i < GPL; ++i) {
-        const int32_t g = i * lpr + l;
-        if (g < a.n_granules) {
-            const Rand128 rnd = philox4x32_10((uint32_t)g, s_lo, s_hi, kCounterTag, a.seed_lo, a.seed_hi);
-            uint32_t lo, hi;
-            if (b == 4) {
-                quantise_granule<4>(x[i], rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
-                store_granule<4>(row, g, a.n_granules, stride, lo, hi);
-            } else if (b == 2) {
-                quantise_granule<2>(x[i], rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
-                store_granule<2>(row, g, a.n_granules, stride, lo, hi);
-            } else {
-                quantise_granule<8>(x[i], rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
-                store_granule<8>(row, g, a.n_granules, stride, lo, hi);
-            }
-        }
+    // (5) codes.  Slots are sorted by (peer, width), so nearly every wave holds a single width.
+    uint8_t *row = a.packed + (valid ? off : 0);
+    if (one_width) {
+        if (b_first == 4)      quantise_row<4, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
+        else if (b_first == 2) quantise_row<2, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
+        else                   quantise_row<8, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
+    } else {
+        if (b == 4)      quantise_row<4, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
+        else if (b == 2) quantise_row<2, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
+        else if (b == 8) quantise_row<8, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
     }
 }
 
@@ -255,6 +294,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_wide_kernel(const QuantA
         mx = fmaxf(mx, __shfl_xor(mx, m, kWave));
     }
     const float levels = (float)((1 << b) - 1);
+    const float levels16 = levels * 65536.0f;
     const RowScale rs = row_scale(mn, mx, levels);
     if (lane == 0) *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
 
@@ -267,22 +307,24 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_wide_kernel(const QuantA
         const Rand128 rnd = philox4x32_10((uint32_t)g, s_lo, s_hi, kCounterTag, a.seed_lo, a.seed_hi);
         uint32_t lo, hi;
         if (b == 4) {
-            quantise_granule<4>(x, rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
+            quantise_granule<4, true>(x, rs.Z, rs.inv16, levels16, rnd, g * 8, a.dim, lo, hi);
             store_granule<4>(row, g, a.n_granules, stride, lo, hi);
         } else if (b == 2) {
-            quantise_granule<2>(x, rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
+            quantise_granule<2, true>(x, rs.Z, rs.inv16, levels16, rnd, g * 8, a.dim, lo, hi);
             store_granule<2>(row, g, a.n_granules, stride, lo, hi);
         } else {
-            quantise_granule<8>(x, rs.Z, rs.inv, levels, rnd, g * 8, a.dim, lo, hi);
+            quantise_granule<8, true>(x, rs.Z, rs.inv16, levels16, rnd, g * 8, a.dim, lo, hi);
             store_granule<8>(row, g, a.n_granules, stride, lo, hi);
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Receive side: one wave per slot; a lane turns VW consecutive codes into VW floats and stores them as one
-// vector, so a wave writes 64*VW*4 contiguous bytes per step.  VW*b divides 32, so the codes of one vector
-// never straddle a 32-bit word of the packed row.
+// Receive side.  A lane turns VW consecutive codes into VW floats and stores them as one vector, so a wave
+// writes 64*VW*4 contiguous bytes per step; VW*b divides 32, so the codes of one vector never straddle a
+// 32-bit word of the packed row.  A wave owns R consecutive slots: lanes 0..R-1 fetch the R slots' index
+// entries in one go, then all R*NV packed words are requested before the first one is decoded, so a wave
+// pays two memory latencies for R rows.
 // ---------------------------------------------------------------------------------------------------------
 struct DequantArgs {
     const uint8_t *packed;
@@ -297,8 +339,85 @@ struct DequantArgs {
     int64_t n_feat_rows, ld;
 };
 
-template <int VW>
+__device__ __forceinline__ int64_t readlane_i64(int64_t v, int lane_id)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)v, lane_id);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)((uint64_t)v >> 32), lane_id);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+template <int VW, int NV, int R>
 __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(const DequantArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t t0 = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * R;      // wave-uniform
+    if (t0 >= a.n_recv) return;
+
+    // lane k < R: index entries of slot t0 + k
+    const int64_t t_mine = t0 + lane < a.n_recv ? t0 + lane : a.n_recv - 1;
+    int32_t my_r = -1, my_b = 0;
+    int64_t my_off = 0;
+    float my_z = 0.0f, my_s = 0.0f;
+    if (lane < R) {
+        my_r = a.halo_idx[t_mine];
+        my_b = a.bits[t_mine];
+        my_off = a.row_offset[t_mine];
+        const float2 zs = *reinterpret_cast<const float2 *>(a.params + 2 * t_mine);
+        my_z = zs.x;
+        my_s = zs.y;
+        const int64_t stride = 4 * (((int64_t)a.dim * my_b + 31) >> 5);
+        const bool ok = t0 + lane < a.n_recv && my_r >= 0 && my_r < a.n_feat_rows &&
+                        (my_b == 2 || my_b == 4 || my_b == 8) && my_off >= 0 && (my_off & 3) == 0 &&
+                        my_off + stride <= a.packed_bytes;
+        if (!ok) my_r = -1;
+    }
+
+    const bool last_ok = ((NV - 1) * kWave + lane) * VW < a.dim;
+    uint32_t w[R][NV];
+    int32_t b_of[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const int32_t r = __builtin_amdgcn_readlane(my_r, k);
+        b_of[k] = __builtin_amdgcn_readlane(my_b, k);
+        const int64_t off = readlane_i64(my_off, k);
+        const uint32_t *words = reinterpret_cast<const uint32_t *>(a.packed + (r >= 0 ? off : 0));
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            w[k][v] = 0u;
+            if (r >= 0 && (v < NV - 1 || last_ok)) {
+                const uint32_t bit = (uint32_t)((v * kWave + lane) * VW) * (uint32_t)b_of[k];
+                w[k][v] = words[bit >> 5] >> (bit & 31u);
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const int32_t r = __builtin_amdgcn_readlane(my_r, k);
+        if (r < 0) continue;
+        const float Z = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_z), k));
+        const float S = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_s), k));
+        const int32_t b = b_of[k];
+        const uint32_t mask = (1u << b) - 1u;
+        float *h = a.feat + (int64_t)r * a.ld;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            if (v < NV - 1 || last_ok) {
+                float y[VW];
+#pragma unroll
+                for (int q = 0; q < VW; ++q) {
+                    const uint32_t code = (w[k][v] >> (q * b)) & mask;
+                    const float scaled = (float)code * S;          // Eq. 5: product rounded, then sum rounded
+                    y[q] = scaled + Z;
+                }
+                store_vec<VW>(h + (v * kWave + lane) * VW, y);
+            }
+        }
+    }
+}
+
+// Any row length: one wave per slot, looping over the row.
+template <int VW>
+__global__ __launch_bounds__(kBlock) void unpack_dequant_long_kernel(const DequantArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t t = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);     // wave-uniform
@@ -345,6 +464,22 @@ hipError_t launch_quantize(const QuantArgs &a, int gpl, dim3 grid, hipStream_t s
 {
     switch (gpl) {
 #define ADAQP_CASE(G) case G: hipLaunchKernelGGL((quantize_pack_kernel<G, VW>), grid, dim3(kBlock), 0, st, a); break;
+        ADAQP_CASE(1) ADAQP_CASE(2) ADAQP_CASE(3) ADAQP_CASE(4)
+        ADAQP_CASE(5) ADAQP_CASE(6) ADAQP_CASE(7) ADAQP_CASE(8)
+#undef ADAQP_CASE
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+constexpr int kDequantRows = 4;      // slots per wave on the receive side
+constexpr int kMaxDequantNv = 8;
+
+template <int VW>
+hipError_t launch_dequant(const DequantArgs &a, int nv, dim3 grid, hipStream_t st)
+{
+    switch (nv) {
+#define ADAQP_CASE(N) case N: hipLaunchKernelGGL((unpack_dequant_kernel<VW, N, kDequantRows>), grid, dim3(kBlock), 0, st, a); break;
         ADAQP_CASE(1) ADAQP_CASE(2) ADAQP_CASE(3) ADAQP_CASE(4)
         ADAQP_CASE(5) ADAQP_CASE(6) ADAQP_CASE(7) ADAQP_CASE(8)
 #undef ADAQP_CASE
@@ -455,11 +590,22 @@ extern "C" int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_by
     a.n_feat_rows = n_feat_rows;
     a.ld = ld;
     hipStream_t st = (hipStream_t)stream;
-    const dim3 grid((unsigned)blocks);
     const int vw = vector_width(feat_dev, ld, dim);
-    if (vw == 4) hipLaunchKernelGGL(unpack_dequant_kernel<4>, grid, dim3(kBlock), 0, st, a);
-    else if (vw == 2) hipLaunchKernelGGL(unpack_dequant_kernel<2>, grid, dim3(kBlock), 0, st, a);
-    else hipLaunchKernelGGL(unpack_dequant_kernel<1>, grid, dim3(kBlock), 0, st, a);
+    const int nv = (dim + kWave * vw - 1) / (kWave * vw);
+    if (nv <= kMaxDequantNv) {
+        const int64_t waves = (n_recv + kDequantRows - 1) / kDequantRows;
+        const dim3 grid((unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock));
+        hipError_t err;
+        if (vw == 4) err = launch_dequant<4>(a, nv, grid, st);
+        else if (vw == 2) err = launch_dequant<2>(a, nv, grid, st);
+        else err = launch_dequant<1>(a, nv, grid, st);
+        ADAQP_HIP_TRY(err);
+        return ADAQP_OK;
+    }
+    const dim3 grid((unsigned)blocks);
+    if (vw == 4) hipLaunchKernelGGL(unpack_dequant_long_kernel<4>, grid, dim3(kBlock), 0, st, a);
+    else if (vw == 2) hipLaunchKernelGGL(unpack_dequant_long_kernel<2>, grid, dim3(kBlock), 0, st, a);
+    else hipLaunchKernelGGL(unpack_dequant_long_kernel<1>, grid, dim3(kBlock), 0, st, a);
     ADAQP_HIP_TRY(hipGetLastError());
     return ADAQP_OK;
 }

@@ -227,7 +227,9 @@ __global__ __launch_bounds__(kBlock) void spmm_merge_kernel(const SpmmArgs a)
 }
 
 // Adds the carries of every split row to the part stored by the piece that finished the row, in piece order.
-// One wave per piece; only the wave of a row's first carry does the work.
+// One wave per piece; only the wave of a row's first carry does the work.  Lanes own the same column slices
+// as in the main kernel, and several carries are in flight at once.
+template <int VW, int NV>
 __global__ __launch_bounds__(kBlock) void spmm_carry_kernel(const SpmmArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -238,11 +240,48 @@ __global__ __launch_bounds__(kBlock) void spmm_carry_kernel(const SpmmArgs a)
     if (item > 0 && uniform_i32(a.carry_row[item - 1]) == r) return;
     int32_t last = item + 1;
     while (last < a.n_items && uniform_i32(a.carry_row[last]) == r) ++last;
+
+    const bool last_ok = ((NV - 1) * kWave + lane) * VW < a.dim;
+    float sum[NV][VW];
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+#pragma unroll
+        for (int k = 0; k < VW; ++k) sum[v][k] = 0.0f;
+    constexpr int kAhead = 4;
+    for (int32_t w0 = item; w0 < last; w0 += kAhead) {
+        float c[kAhead][NV][VW];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int32_t w = w0 + u < last ? w0 + u : last - 1;
+            const float *slot = a.carry + (int64_t)w * a.carry_ld;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                if (v < NV - 1 || last_ok) {
+                    load_vec<VW>(slot + (v * kWave + lane) * VW, c[u][v]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < VW; ++k) c[u][v][k] = 0.0f;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u)
+            if (w0 + u < last)
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
+#pragma unroll
+                    for (int k = 0; k < VW; ++k) sum[v][k] += c[u][v][k];
+    }
     float *o = a.out + (int64_t)r * a.ldo;
-    for (int32_t c = lane; c < a.dim; c += kWave) {
-        float sum = 0.0f;
-        for (int32_t w = item; w < last; ++w) sum += a.carry[(int64_t)w * a.carry_ld + c];
-        o[c] = o[c] + sum;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        if (v < NV - 1 || last_ok) {
+            float cur[VW];
+            load_vec<VW>(o + (v * kWave + lane) * VW, cur);
+#pragma unroll
+            for (int k = 0; k < VW; ++k) cur[k] = cur[k] + sum[v][k];
+            store_vec<VW>(o + (v * kWave + lane) * VW, cur);
+        }
     }
 }
 
@@ -271,6 +310,9 @@ hipError_t launch_merge(const SpmmArgs &a, dim3 grid, hipStream_t st)
 {
     constexpr int U = NV >= 4 ? 4 : (NV >= 2 ? 8 : 16);
     hipLaunchKernelGGL((spmm_merge_kernel<VW, NV, U>), grid, dim3(kBlock), 0, st, a);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((spmm_carry_kernel<VW, NV>), grid, dim3(kBlock), 0, st, a);
     return hipGetLastError();
 }
 
@@ -359,8 +401,6 @@ extern "C" int adaqp_spmm_csr(const int64_t *rowptr_dev, const int32_t *col_dev,
         else if (vw == 2) err = launch_merge_nv<2>(a, nv, grid, st);
         else err = launch_merge_nv<1>(a, nv, grid, st);
         ADAQP_HIP_TRY(err);
-        hipLaunchKernelGGL(spmm_carry_kernel, grid, dim3(kBlock), 0, st, a);
-        ADAQP_HIP_TRY(hipGetLastError());
     }
     return ADAQP_OK;
 }
