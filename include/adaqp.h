@@ -26,7 +26,13 @@
  *   - A count of zero is a successful no-op.
  *   - Inputs must be finite.  A row's range max - min must be 0 or at least 2^-100 (otherwise the fp32
  *     reciprocal overflows; codes stay in range but are unspecified).
- *   - Feature matrices are fp32 row-major with a leading dimension ld >= dim, counted in elements.
+ *   - Feature matrices are fp32 row-major with a leading dimension (pitch) ld >= dim, counted in elements.
+ *   - Preferred layout ("line-padded"): base pointer 128-byte aligned and ld a multiple of 32, so that every
+ *     row starts on a 128-byte line and covers whole lines.  Any other layout is accepted and gives the same
+ *     values, but partial-line writes are slower.  For a line-padded OUTPUT matrix the calls below write the
+ *     rows they produce in whole lines: columns [dim, 32*ceil(dim/32)) of a written row are set to +0.0f
+ *     (columns beyond that, and rows that are not written, stay untouched).  For any other output layout
+ *     only columns [0, dim) are written.  Padding columns of INPUT matrices may hold anything.
  */
 #ifndef ADAQP_H
 #define ADAQP_H
@@ -103,13 +109,22 @@ int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, int64_t ld, 
 /* set" of Sec. 5.                                                                                         */
 /* ---------------------------------------------------------------------------------------------------- */
 
+/* Host only: the order in which the receive side should visit its slots so that consecutive waves write
+ * ascending rows (DRAM takes sequential row writes faster than scattered ones).  order_out[k] = the slot
+ * visited at position k; slots sorted by halo_idx_host, ties by slot index.  n <= 2^31 - 1.
+ * Errors: EINVAL, ESIZE. */
+int adaqp_plan_recv_order(int64_t n, const int32_t *halo_idx_host, int32_t *order_out);
+
 /* For each slot t in [0, n_recv):  feat[halo_idx[t], j] = (float)code_j * S + Z   (product rounded, then sum
  * rounded), j in [0, dim), with {Z, S} = params[t] and code_j read from packed + row_offset[t].
- * Columns dim .. ld-1 and rows not listed are left untouched.  Out-of-range slots are skipped as above.
- * Errors: EINVAL, EHIP. */
+ * Rows not listed are left untouched; padding columns as described under "Preferred layout".
+ *   order_dev  optional [n_recv] int32 permutation of the slots (adaqp_plan_recv_order); NULL = slot order.
+ *              It only changes which wave handles which slot, never a value; entries outside [0, n_recv)
+ *              are skipped.  halo_idx must not list a row twice.
+ * Out-of-range slots are skipped as above.  Errors: EINVAL, ESIZE, EHIP. */
 int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
                          const uint8_t *bits_dev, const int64_t *row_offset_dev,
-                         const int32_t *halo_idx_dev, int64_t n_recv, int32_t dim,
+                         const int32_t *halo_idx_dev, const int32_t *order_dev, int64_t n_recv, int32_t dim,
                          float *feat_dev, int64_t n_feat_rows, int64_t ld, void *stream);
 
 /* ---------------------------------------------------------------------------------------------------- */
@@ -130,7 +145,8 @@ int adaqp_spmm_workspace_bytes(int64_t n_rows, int64_t nnz, int32_t dim, int64_t
  *   nnz_range  number of entries in rows [row_begin, row_end) if the caller knows it, else -1 (nnz is
  *              used).  It only sizes the launch; the exact count is re-read from rowptr on the device.
  *   H_dev      [n_cols, ldh] fp32; entries with col outside [0, n_cols) are skipped
- *   out_dev    [>= row_end, ldo] fp32; only rows [row_begin, row_end), columns [0, dim) are written
+ *   out_dev    [>= row_end, ldo] fp32; only rows [row_begin, row_end) are written (columns [0, dim), plus
+ *              zeroed padding when H and out are both line-padded, see "Preferred layout")
  *   workspace_dev / workspace_bytes   scratch of at least adaqp_spmm_workspace_bytes(row_end - row_begin,
  *              nnz_range or nnz, dim) bytes, 256-byte aligned; contents need not be initialised and are
  *              undefined afterwards.  Two launches that may run concurrently need distinct workspaces.
@@ -182,6 +198,7 @@ typedef struct adaqp_layer_desc {
     const uint8_t *bits_dev;
     const int64_t *row_offset_dev;
     const int32_t *halo_idx_dev;    /* forward only: destination rows of the received slots */
+    const int32_t *recv_order_dev;  /* forward only, optional: adaqp_plan_recv_order of halo_idx */
     int64_t n_send;
     uint64_t seed;
     uint8_t *packed_dev;   float *params_dev;           /* send buffers */

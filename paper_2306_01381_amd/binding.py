@@ -44,6 +44,7 @@ class LayerDesc(ctypes.Structure):
         ("feat_dev", _vp), ("n_feat_rows", _i64), ("ld", _i64), ("dim", _i32),
         ("out_dev", _vp), ("ldo", _i64),
         ("send_idx_dev", _vp), ("bits_dev", _vp), ("row_offset_dev", _vp), ("halo_idx_dev", _vp),
+        ("recv_order_dev", _vp),
         ("n_send", _i64), ("seed", _u64),
         ("packed_dev", _vp), ("params_dev", _vp), ("recv_packed_dev", _vp), ("recv_params_dev", _vp),
         ("packed_bytes", _i64),
@@ -62,7 +63,8 @@ _SIGNATURES = {
     "adaqp_row_stride": (_i64, [_i32, _i32]),
     "adaqp_plan_layout": (ctypes.c_int, [_i64, _i32, _vp, _vp, _i32, _vp, _vp, _vp]),
     "adaqp_quantize_pack": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _u64, _vp, _i64, _vp, _vp]),
-    "adaqp_unpack_dequant": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i64, _vp]),
+    "adaqp_plan_recv_order": (ctypes.c_int, [_i64, _vp, _vp]),
+    "adaqp_unpack_dequant": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i64, _vp]),
     "adaqp_spmm_workspace_bytes": (ctypes.c_int, [_i64, _i64, _i32, ctypes.POINTER(_i64)]),
     "adaqp_spmm_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
                                       _vp, _i64, _vp, _i64, _vp]),
@@ -150,15 +152,25 @@ def adaqp_quantize_pack(feat: torch.Tensor, dim: int, send_idx: torch.Tensor, bi
            "adaqp_quantize_pack")
 
 
+def adaqp_plan_recv_order(halo_idx_host: np.ndarray) -> np.ndarray:
+    """Host-only.  Returns the int32 visiting order of the receive slots (ascending destination rows)."""
+    halo = np.ascontiguousarray(halo_idx_host, dtype=np.int32)
+    order = np.zeros(halo.shape[0], dtype=np.int32)
+    _check(lib().adaqp_plan_recv_order(halo.shape[0], halo.ctypes.data, order.ctypes.data), "adaqp_plan_recv_order")
+    return order
+
+
 def adaqp_unpack_dequant(packed: torch.Tensor, params: torch.Tensor, bits: torch.Tensor,
                          row_offset: torch.Tensor, halo_idx: torch.Tensor, dim: int, feat: torch.Tensor,
+                         order: Optional[torch.Tensor] = None,
                          stream: Optional[torch.cuda.Stream] = None) -> None:
     fp, n_rows, ld = _matrix(feat, "feat")
     n = halo_idx.shape[0]
     _check(lib().adaqp_unpack_dequant(_dev(packed, torch.uint8, "packed"), packed.numel(),
                                       _dev(params, torch.float32, "params"), _dev(bits, torch.uint8, "bits"),
                                       _dev(row_offset, torch.int64, "row_offset"),
-                                      _dev(halo_idx, torch.int32, "halo_idx"), n, dim, fp, n_rows, ld,
+                                      _dev(halo_idx, torch.int32, "halo_idx"), _dev(order, torch.int32, "order"),
+                                      n, dim, fp, n_rows, ld,
                                       _stream(stream)),
            "adaqp_unpack_dequant")
 

@@ -10,10 +10,8 @@
 // holding granules l, l + LPR, l + 2*LPR, ... (GPL of them) in registers, so that at each step the LPR
 // lanes of a row read LPR*32 contiguous bytes.  LPR and GPL are chosen on the host so that LPR*GPL barely
 // exceeds dim/8 (D=602: 16 x 5, D=256: 8 x 4, D=300: 8 x 5, D=128: 4 x 4); a wave carries 64/LPR rows.
-// Order of work inside a wave: (1) issue the loads of the slot's index entries; (2) while they are in
-// flight, run Philox for all GPL granules - the random values depend only on (seed, slot, column), not on
-// memory; (3) issue all row loads; (4) min / max in registers, xor-shuffle reduction over the row's lanes,
-// (Z, S, inv) computed redundantly by every lane; (5) codes, packed in registers, stored.
+// min / max are reduced in registers and over the row's lanes with xor shuffles, (Z, S, inv) are computed
+// redundantly by every lane, the codes are packed in registers and stored.
 // 32-bit integer multiplies issue at full rate on gfx950 (measured), so a Philox call costs about 60 VALU
 // issue slots per lane, the rest of a granule about as much again.
 //
@@ -50,12 +48,6 @@ __device__ __forceinline__ Rand128 philox4x32_10(uint32_t c0, uint32_t c1, uint3
 
 constexpr uint32_t kCounterTag = 0x41645150u;
 
-// Pins a value to this point of the program: the optimiser may neither sink its computation below nor
-// rematerialise it later.
-__device__ __forceinline__ void pin(Rand128 &r)
-{
-    asm volatile("" : "+v"(r.w0), "+v"(r.w1), "+v"(r.w2), "+v"(r.w3));
-}
 
 struct QuantArgs {
     const float *feat;
@@ -171,8 +163,19 @@ __device__ __forceinline__ void quantise_row(const float (&x)[GPL][8], const Ran
     }
 }
 
+// Pins a value to this point of the program: the optimiser may neither sink its computation below nor
+// rematerialise it later.
+__device__ __forceinline__ void pin(Rand128 &r)
+{
+    asm volatile("" : "+v"(r.w0), "+v"(r.w1), "+v"(r.w2), "+v"(r.w3));
+}
+
 // ---------------------------------------------------------------------------------------------------------
-// Register-resident rows: GPL granules per lane, LPR = 2^lpr_log2 lanes per row.
+// Register-resident rows: GPL granules per lane, LPR = 2^lpr_log2 lanes per row, 64/LPR rows per wave.
+// Order of work inside a wave: (1) issue the loads of the slots' index entries; (2) while they are in
+// flight, run Philox for the first granules - the rounding values depend only on (seed, slot, column), not
+// on memory; (3) issue all row loads; (4) Philox for the remaining granules while the rows stream in;
+// (5) min / max, scale, codes, stores.
 // ---------------------------------------------------------------------------------------------------------
 template <int GPL, int VW>
 __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a)
@@ -191,9 +194,8 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
     const int32_t b = a.bits[s_safe];
     const int64_t off = a.row_offset[s_safe];
 
-    // (2) rounding values of the lane's granules.  They depend on (seed, slot, column) only, not on memory:
-    // the first kEarly calls run while the index entries are in flight, the rest after the row loads have
-    // been issued (the scheduling barriers keep the compiler from sinking them behind the loads' wait).
+    // (2) rounding values of the lane's first granules (the barriers and pins keep the compiler from sinking
+    // the arithmetic behind the wait for the rows)
     constexpr int kEarly = GPL < 2 ? GPL : 2;
     Rand128 rnd[GPL];
     const uint32_t s_lo = (uint32_t)s, s_hi = (uint32_t)((uint64_t)s >> 32);
@@ -210,19 +212,22 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
     const float *h = a.feat + (valid ? (int64_t)r_raw * a.ld : 0);
 
     // (3) gather the lane's granules.  Only the last step can reach past the row; there the column is clamped
-    // to the row's last vector, which repeats real elements and so leaves min and max alone.
+    // to the vector holding the row's last element, and elements past dim (row padding, the pitch is a
+    // multiple of VW) are replaced by that vector's first element: only real elements enter min and max.
     float x[GPL][8];
+    const int32_t last_vec = ((a.dim - 1) / VW) * VW;
 #pragma unroll
     for (int i = 0; i < GPL; ++i) {
         const int32_t c0 = (i * lpr + l) * 8;
 #pragma unroll
         for (int v = 0; v < 8 / VW; ++v) {
             int32_t c = c0 + v * VW;
-            if (i == GPL - 1) c = c < a.dim - VW ? c : a.dim - VW;
+            if (i == GPL - 1) c = c < last_vec ? c : last_vec;
             load_vec<VW>(h + c, &x[i][v * VW]);
         }
     }
     __builtin_amdgcn_sched_barrier(0);
+    // (4)
 #pragma unroll
     for (int i = kEarly; i < GPL; ++i) {
         rnd[i] = philox4x32_10((uint32_t)(i * lpr + l), s_lo, s_hi, kCounterTag, a.seed_lo, a.seed_hi);
@@ -230,7 +235,18 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    // (4) row minimum / maximum
+    // (5) row minimum / maximum
+    if (VW > 1) {
+        const int32_t c0 = ((GPL - 1) * lpr + l) * 8;
+#pragma unroll
+        for (int v = 0; v < 8 / VW; ++v) {
+            int32_t c = c0 + v * VW;
+            c = c < last_vec ? c : last_vec;
+#pragma unroll
+            for (int k = 1; k < VW; ++k)
+                if (c + k >= a.dim) x[GPL - 1][v * VW + k] = x[GPL - 1][v * VW];
+        }
+    }
     float mn = x[0][0], mx = x[0][0];
 #pragma unroll
     for (int i = 0; i < GPL; ++i)
@@ -252,7 +268,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
     const RowScale rs = row_scale(mn, mx, levels);
     if (valid && l == 0) *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
 
-    // (5) codes.  Slots are sorted by (peer, width), so nearly every wave holds a single width.
+    // codes.  Slots are sorted by (peer, width), so nearly every wave holds a single width.
     uint8_t *row = a.packed + (valid ? off : 0);
     if (one_width) {
         if (b_first == 4)      quantise_row<4, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
@@ -333,8 +349,9 @@ struct DequantArgs {
     const uint8_t *bits;
     const int64_t *row_offset;
     const int32_t *halo_idx;
+    const int32_t *order;       // optional: slot handled at position k (ascending destination rows)
     int64_t n_recv;
-    int32_t dim;
+    int32_t dim, write_dim;     // write_dim > dim: columns [dim, write_dim) receive zeros (whole 128-byte lines)
     float *feat;
     int64_t n_feat_rows, ld;
 };
@@ -353,12 +370,18 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(const DequantArg
     const int64_t t0 = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * R;      // wave-uniform
     if (t0 >= a.n_recv) return;
 
-    // lane k < R: index entries of slot t0 + k
-    const int64_t t_mine = t0 + lane < a.n_recv ? t0 + lane : a.n_recv - 1;
+    // lane k < R: index entries of the slot at position t0 + k
+    int64_t t_mine = t0 + lane < a.n_recv ? t0 + lane : a.n_recv - 1;
     int32_t my_r = -1, my_b = 0;
     int64_t my_off = 0;
     float my_z = 0.0f, my_s = 0.0f;
     if (lane < R) {
+        bool in_list = true;
+        if (a.order) {
+            const int32_t o = a.order[t_mine];
+            in_list = o >= 0 && o < a.n_recv;
+            t_mine = in_list ? o : 0;
+        }
         my_r = a.halo_idx[t_mine];
         my_b = a.bits[t_mine];
         my_off = a.row_offset[t_mine];
@@ -366,13 +389,16 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(const DequantArg
         my_z = zs.x;
         my_s = zs.y;
         const int64_t stride = 4 * (((int64_t)a.dim * my_b + 31) >> 5);
-        const bool ok = t0 + lane < a.n_recv && my_r >= 0 && my_r < a.n_feat_rows &&
+        const bool ok = in_list && t0 + lane < a.n_recv && my_r >= 0 && my_r < a.n_feat_rows &&
                         (my_b == 2 || my_b == 4 || my_b == 8) && my_off >= 0 && (my_off & 3) == 0 &&
                         my_off + stride <= a.packed_bytes;
         if (!ok) my_r = -1;
     }
 
-    const bool last_ok = ((NV - 1) * kWave + lane) * VW < a.dim;
+    const bool last_ok = ((NV - 1) * kWave + lane) * VW < a.write_dim;
+    // Every packed word is requested before the first one is looked at.  The loads are unconditional (a lane
+    // past the row re-reads the row's last word, a skipped slot reads the buffer's first word) so that they
+    // form one straight run of instructions with a single wait behind it.
     uint32_t w[R][NV];
     int32_t b_of[R];
 #pragma unroll
@@ -381,13 +407,12 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(const DequantArg
         b_of[k] = __builtin_amdgcn_readlane(my_b, k);
         const int64_t off = readlane_i64(my_off, k);
         const uint32_t *words = reinterpret_cast<const uint32_t *>(a.packed + (r >= 0 ? off : 0));
+        const uint32_t last_word = r >= 0 ? (uint32_t)(((int64_t)a.dim * b_of[k] - 1) >> 5) : 0u;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            w[k][v] = 0u;
-            if (r >= 0 && (v < NV - 1 || last_ok)) {
-                const uint32_t bit = (uint32_t)((v * kWave + lane) * VW) * (uint32_t)b_of[k];
-                w[k][v] = words[bit >> 5] >> (bit & 31u);
-            }
+            const uint32_t bit = (uint32_t)((v * kWave + lane) * VW) * (uint32_t)b_of[k];
+            const uint32_t idx = (bit >> 5) < last_word ? (bit >> 5) : last_word;
+            w[k][v] = words[idx];
         }
     }
 #pragma unroll
@@ -403,11 +428,14 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(const DequantArg
         for (int v = 0; v < NV; ++v) {
             if (v < NV - 1 || last_ok) {
                 float y[VW];
+                const uint32_t bit = (uint32_t)((v * kWave + lane) * VW) * (uint32_t)b;
+                const uint32_t word = w[k][v] >> (bit & 31u);
 #pragma unroll
                 for (int q = 0; q < VW; ++q) {
-                    const uint32_t code = (w[k][v] >> (q * b)) & mask;
+                    const uint32_t code = (word >> (q * b)) & mask;
                     const float scaled = (float)code * S;          // Eq. 5: product rounded, then sum rounded
                     y[q] = scaled + Z;
+                    if (v == NV - 1 && (v * kWave + lane) * VW + q >= a.dim) y[q] = 0.0f;   // row padding
                 }
                 store_vec<VW>(h + (v * kWave + lane) * VW, y);
             }
@@ -420,8 +448,12 @@ template <int VW>
 __global__ __launch_bounds__(kBlock) void unpack_dequant_long_kernel(const DequantArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t t = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);     // wave-uniform
+    int64_t t = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);           // wave-uniform
     if (t >= a.n_recv) return;
+    if (a.order) {
+        t = a.order[t];
+        if (t < 0 || t >= a.n_recv) return;
+    }
     const int32_t r = a.halo_idx[t];
     const int32_t b = a.bits[t];
     const int64_t off = a.row_offset[t];
@@ -447,17 +479,22 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_long_kernel(const Dequa
         }
         store_vec<VW>(h + c, y);
     }
+    for (int32_t c = a.dim + lane; c < a.write_dim; c += kWave) h[c] = 0.0f;           // row padding
 }
 
 constexpr int kMaxGpl = 8;
 
-// Largest vector width (floats) such that every row start and every vector inside a row is naturally aligned.
-int vector_width(const void *base, int64_t ld, int32_t dim)
+// Largest vector width (floats) such that every row start is naturally aligned.  `whole_vectors`: the width
+// must also divide dim (needed where a vector may not spill into the row's padding).
+int vector_width(const void *base, int64_t ld, int32_t dim, bool whole_vectors)
 {
-    if (dim % 4 == 0 && ld % 4 == 0 && aligned_to(base, 16)) return 4;
-    if (dim % 2 == 0 && ld % 2 == 0 && aligned_to(base, 8)) return 2;
+    if (ld % 4 == 0 && aligned_to(base, 16) && (!whole_vectors || dim % 4 == 0)) return 4;
+    if (ld % 2 == 0 && aligned_to(base, 8) && (!whole_vectors || dim % 2 == 0)) return 2;
     return 1;
 }
+
+// Rows start on 128-byte lines and the pitch is a whole number of lines: the layout this library is built for.
+bool line_padded(const void *base, int64_t ld) { return ld % 32 == 0 && aligned_to(base, 128); }
 
 template <int VW>
 hipError_t launch_quantize(const QuantArgs &a, int gpl, dim3 grid, hipStream_t st)
@@ -475,11 +512,11 @@ hipError_t launch_quantize(const QuantArgs &a, int gpl, dim3 grid, hipStream_t s
 constexpr int kDequantRows = 4;      // slots per wave on the receive side
 constexpr int kMaxDequantNv = 8;
 
-template <int VW>
+template <int VW, int R>
 hipError_t launch_dequant(const DequantArgs &a, int nv, dim3 grid, hipStream_t st)
 {
     switch (nv) {
-#define ADAQP_CASE(N) case N: hipLaunchKernelGGL((unpack_dequant_kernel<VW, N, kDequantRows>), grid, dim3(kBlock), 0, st, a); break;
+#define ADAQP_CASE(N) case N: hipLaunchKernelGGL((unpack_dequant_kernel<VW, N, R>), grid, dim3(kBlock), 0, st, a); break;
         ADAQP_CASE(1) ADAQP_CASE(2) ADAQP_CASE(3) ADAQP_CASE(4)
         ADAQP_CASE(5) ADAQP_CASE(6) ADAQP_CASE(7) ADAQP_CASE(8)
 #undef ADAQP_CASE
@@ -526,7 +563,7 @@ extern "C" int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, i
     a.lpr_log2 = 0;
     hipStream_t st = (hipStream_t)stream;
 
-    // lanes per row / granules per lane: least padding first, then the most granules per lane
+    // lanes per row / granules per lane: least padding first, then the count closest to four granules
     int best_k = -1, best_gpl = 0;
     int64_t best_waste = INT64_MAX;
     for (int k = 0; k <= 6; ++k) {
@@ -534,7 +571,8 @@ extern "C" int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, i
         const int gpl = (a.n_granules + lpr - 1) / lpr;
         if (gpl > kMaxGpl) continue;
         const int64_t waste = (int64_t)lpr * gpl - a.n_granules;
-        if (waste < best_waste || (waste == best_waste && gpl <= 5 && gpl > best_gpl)) {
+        const bool closer = (gpl > 4 ? gpl - 4 : 4 - gpl) < (best_gpl > 4 ? best_gpl - 4 : 4 - best_gpl);
+        if (waste < best_waste || (waste == best_waste && closer)) {
             best_waste = waste;
             best_k = k;
             best_gpl = gpl;
@@ -552,7 +590,7 @@ extern "C" int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, i
     const int64_t blocks = (n_send + rows_per_block - 1) / rows_per_block;
     if (blocks > INT32_MAX) return ADAQP_ESIZE;
     const dim3 grid((unsigned)blocks);
-    const int vw = vector_width(feat_dev, ld, dim);
+    const int vw = vector_width(feat_dev, ld, dim, false);
     hipError_t err;
     if (vw == 4) err = launch_quantize<4>(a, best_gpl, grid, st);
     else if (vw == 2) err = launch_quantize<2>(a, best_gpl, grid, st);
@@ -563,8 +601,8 @@ extern "C" int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, i
 
 extern "C" int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
                                     const uint8_t *bits_dev, const int64_t *row_offset_dev,
-                                    const int32_t *halo_idx_dev, int64_t n_recv, int32_t dim,
-                                    float *feat_dev, int64_t n_feat_rows, int64_t ld, void *stream)
+                                    const int32_t *halo_idx_dev, const int32_t *order_dev, int64_t n_recv,
+                                    int32_t dim, float *feat_dev, int64_t n_feat_rows, int64_t ld, void *stream)
 {
     if (n_recv < 0 || dim <= 0 || ld < dim || n_feat_rows < 0 || packed_bytes < 0) return ADAQP_EINVAL;
     if (n_recv == 0) return ADAQP_OK;
@@ -572,8 +610,10 @@ extern "C" int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_by
         return ADAQP_EINVAL;
     if (n_feat_rows == 0) return ADAQP_EINVAL;
     if (!aligned_to(feat_dev, 4) || !aligned_to(params_dev, 8) || !aligned_to(packed_dev, 4) ||
-        !aligned_to(halo_idx_dev, 4) || !aligned_to(row_offset_dev, 8))
+        !aligned_to(halo_idx_dev, 4) || !aligned_to(row_offset_dev, 8) || !aligned_to(order_dev, 4))
         return ADAQP_EINVAL;
+    if (order_dev && n_recv > INT32_MAX) return ADAQP_ESIZE;
+    if (packed_bytes < 4) return ADAQP_OK;          // no row fits: every slot would be skipped
     const int64_t blocks = (n_recv + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > INT32_MAX) return ADAQP_ESIZE;
 
@@ -584,27 +624,36 @@ extern "C" int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_by
     a.bits = bits_dev;
     a.row_offset = row_offset_dev;
     a.halo_idx = halo_idx_dev;
+    a.order = order_dev;
     a.n_recv = n_recv;
     a.dim = dim;
+    a.write_dim = dim;
     a.feat = feat_dev;
     a.n_feat_rows = n_feat_rows;
     a.ld = ld;
     hipStream_t st = (hipStream_t)stream;
-    const int vw = vector_width(feat_dev, ld, dim);
-    const int nv = (dim + kWave * vw - 1) / (kWave * vw);
+    // line-padded rows are written in whole 128-byte lines (the padding receives zeros): partial-line
+    // writes cost a read-modify-write in the memory system
+    const bool whole_lines = line_padded(feat_dev, ld);
+    const int32_t write_dim = whole_lines ? (int32_t)((((int64_t)dim + 31) / 32) * 32) : dim;
+    const int vw = vector_width(feat_dev, ld, dim, !whole_lines);
+    const int nv = (write_dim + kWave * vw - 1) / (kWave * vw);
     if (nv <= kMaxDequantNv) {
+        a.write_dim = write_dim;
         const int64_t waves = (n_recv + kDequantRows - 1) / kDequantRows;
         const dim3 grid((unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock));
         hipError_t err;
-        if (vw == 4) err = launch_dequant<4>(a, nv, grid, st);
-        else if (vw == 2) err = launch_dequant<2>(a, nv, grid, st);
-        else err = launch_dequant<1>(a, nv, grid, st);
+        if (vw == 4) err = launch_dequant<4, kDequantRows>(a, nv, grid, st);
+        else if (vw == 2) err = launch_dequant<2, kDequantRows>(a, nv, grid, st);
+        else err = launch_dequant<1, kDequantRows>(a, nv, grid, st);
         ADAQP_HIP_TRY(err);
         return ADAQP_OK;
     }
     const dim3 grid((unsigned)blocks);
-    if (vw == 4) hipLaunchKernelGGL(unpack_dequant_long_kernel<4>, grid, dim3(kBlock), 0, st, a);
-    else if (vw == 2) hipLaunchKernelGGL(unpack_dequant_long_kernel<2>, grid, dim3(kBlock), 0, st, a);
+    a.write_dim = write_dim;
+    const int vw_long = vector_width(feat_dev, ld, dim, true);
+    if (vw_long == 4) hipLaunchKernelGGL(unpack_dequant_long_kernel<4>, grid, dim3(kBlock), 0, st, a);
+    else if (vw_long == 2) hipLaunchKernelGGL(unpack_dequant_long_kernel<2>, grid, dim3(kBlock), 0, st, a);
     else hipLaunchKernelGGL(unpack_dequant_long_kernel<1>, grid, dim3(kBlock), 0, st, a);
     ADAQP_HIP_TRY(hipGetLastError());
     return ADAQP_OK;

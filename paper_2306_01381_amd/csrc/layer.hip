@@ -4,6 +4,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
+
 #include "common.hpp"
 
 namespace adaqp {
@@ -85,6 +87,18 @@ extern "C" int adaqp_plan_layout(int64_t n, int32_t dim, const uint8_t *bits_hos
         seg_begin = seg_end;
     }
     peer_byte_ptr_out[n_peers] = bytes;
+    return ADAQP_OK;
+}
+
+extern "C" int adaqp_plan_recv_order(int64_t n, const int32_t *halo_idx_host, int32_t *order_out)
+{
+    if (n < 0) return ADAQP_EINVAL;
+    if (n == 0) return ADAQP_OK;
+    if (!halo_idx_host || !order_out) return ADAQP_EINVAL;
+    if (n > INT32_MAX) return ADAQP_ESIZE;
+    for (int64_t i = 0; i < n; ++i) order_out[i] = (int32_t)i;
+    std::stable_sort(order_out, order_out + n,
+                     [halo_idx_host](int32_t x, int32_t y) { return halo_idx_host[x] < halo_idx_host[y]; });
     return ADAQP_OK;
 }
 
@@ -202,7 +216,7 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
         }
         ADAQP_STEP(loop_back(d, msg));
         ADAQP_STEP(adaqp_unpack_dequant(d->recv_packed_dev, d->packed_bytes, d->recv_params_dev, d->bits_dev,
-                                        d->row_offset_dev, d->halo_idx_dev, d->n_send, d->dim, d->feat_dev,
+                                        d->row_offset_dev, d->halo_idx_dev, d->recv_order_dev, d->n_send, d->dim, d->feat_dev,
                                         d->n_feat_rows, d->ld, msg));
         if (d->schedule == ADAQP_SERIAL) ADAQP_STEP(aggregate(d, true, msg));
         ADAQP_STEP(aggregate(d, false, msg));

@@ -29,7 +29,7 @@ struct SpmmArgs {
     int32_t n_rows;             // rows in the range
     const float *H;
     int64_t n_cols, ldh;
-    int32_t dim;
+    int32_t dim, wdim;          // wdim >= dim: columns [dim, wdim) of a written row receive zeros (whole lines)
     float *out;                 // already offset to the first row of the range
     int64_t ldo;
     int32_t *carry_row;         // [n_items]
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(kBlock) void spmm_merge_kernel(const SpmmArgs a)
     const int32_t n_edges = (int32_t)((d1 - i1) - j0);      // entries in the piece
 
     // per-lane slice of a row: vectors v*64 + lane, v < NV; only the last one can fall off the row
-    const bool last_ok = ((NV - 1) * kWave + lane) * VW < a.dim;
+    const bool last_ok = ((NV - 1) * kWave + lane) * VW < a.wdim;
 
     float acc[NV][VW];
 #pragma unroll
@@ -152,6 +152,11 @@ __global__ __launch_bounds__(kBlock) void spmm_merge_kernel(const SpmmArgs a)
 
     auto flush_row = [&]() {
         float *o = a.out + row * a.ldo;
+        if (a.wdim > a.dim) {                                   // row padding: whatever was gathered there is dropped
+#pragma unroll
+            for (int k = 0; k < VW; ++k)
+                if (((NV - 1) * kWave + lane) * VW + k >= a.dim) acc[NV - 1][k] = 0.0f;
+        }
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             if (v < NV - 1 || last_ok) store_vec<VW>(o + (v * kWave + lane) * VW, acc[v]);
@@ -241,7 +246,7 @@ __global__ __launch_bounds__(kBlock) void spmm_carry_kernel(const SpmmArgs a)
     int32_t last = item + 1;
     while (last < a.n_items && uniform_i32(a.carry_row[last]) == r) ++last;
 
-    const bool last_ok = ((NV - 1) * kWave + lane) * VW < a.dim;
+    const bool last_ok = ((NV - 1) * kWave + lane) * VW < a.wdim;
     float sum[NV][VW];
 #pragma unroll
     for (int v = 0; v < NV; ++v)
@@ -279,7 +284,10 @@ __global__ __launch_bounds__(kBlock) void spmm_carry_kernel(const SpmmArgs a)
             float cur[VW];
             load_vec<VW>(o + (v * kWave + lane) * VW, cur);
 #pragma unroll
-            for (int k = 0; k < VW; ++k) cur[k] = cur[k] + sum[v][k];
+            for (int k = 0; k < VW; ++k) {
+                cur[k] = cur[k] + sum[v][k];
+                if (v == NV - 1 && (v * kWave + lane) * VW + k >= a.dim) cur[k] = 0.0f;      // row padding
+            }
             store_vec<VW>(o + (v * kWave + lane) * VW, cur);
         }
     }
@@ -299,7 +307,7 @@ bool geometry(int64_t n_rows, int64_t nnz, int32_t dim, Geometry *g)
     const int64_t items = (total + per - 1) / per;
     if (items > (int64_t)1 << 30) return false;
     g->n_items = (int32_t)items;
-    g->carry_ld = ((int64_t)dim + 3) / 4 * 4;
+    g->carry_ld = ((int64_t)dim + 31) / 32 * 32;
     g->carry_off = (items * 4 + 255) / 256 * 256;
     g->bytes = g->carry_off + (items * g->carry_ld * 4 + 255) / 256 * 256;
     return true;
@@ -369,9 +377,13 @@ extern "C" int adaqp_spmm_csr(const int64_t *rowptr_dev, const int32_t *col_dev,
     if (g.bytes > 0 && (!workspace_dev || !aligned_to(workspace_dev, 256))) return ADAQP_EINVAL;
     if (workspace_bytes < g.bytes) return ADAQP_ESIZE;
 
-    // vector width: every row start of H and out and of the carry slots must be naturally aligned
+    // vector width: every row start of H and out and of the carry slots must be naturally aligned, and a
+    // vector must not spill past dim - unless both matrices are line-padded (rows start on 128-byte lines,
+    // pitch a whole number of lines): then rows are read and written in whole lines, padding written as zero
+    const bool whole_lines = ldh % 32 == 0 && ldo % 32 == 0 && aligned_to(H_dev, 128) && aligned_to(out_dev, 128);
     int vw = 1;
-    if (dim % 4 == 0 && ldh % 4 == 0 && ldo % 4 == 0 && aligned_to(H_dev, 16) && aligned_to(out_dev, 16)) vw = 4;
+    if (whole_lines) vw = 4;
+    else if (dim % 4 == 0 && ldh % 4 == 0 && ldo % 4 == 0 && aligned_to(H_dev, 16) && aligned_to(out_dev, 16)) vw = 4;
     else if (dim % 2 == 0 && ldh % 2 == 0 && ldo % 2 == 0 && aligned_to(H_dev, 8) && aligned_to(out_dev, 8)) vw = 2;
 
     hipStream_t st = (hipStream_t)stream;
@@ -388,13 +400,14 @@ extern "C" int adaqp_spmm_csr(const int64_t *rowptr_dev, const int32_t *col_dev,
         a.n_cols = n_cols;
         a.ldh = ldh;
         a.dim = cdim;
+        a.wdim = whole_lines ? (cdim + 31) / 32 * 32 : cdim;
         a.out = out_dev + row_begin * ldo + c0;
         a.ldo = ldo;
         a.carry_row = reinterpret_cast<int32_t *>(workspace_dev);
         a.carry = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace_dev) + g.carry_off);
         a.carry_ld = g.carry_ld;
         a.n_items = g.n_items;
-        const int nv = (cdim + kWave * vw - 1) / (kWave * vw);
+        const int nv = (a.wdim + kWave * vw - 1) / (kWave * vw);
         const dim3 grid((unsigned)((g.n_items + kWavesPerBlock - 1) / kWavesPerBlock));
         hipError_t err;
         if (vw == 4) err = launch_merge_nv<4>(a, nv, grid, st);

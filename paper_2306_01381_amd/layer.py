@@ -64,10 +64,23 @@ class SendPlan:
         self.bits = torch.from_numpy(self.bits_host).to(device)
         self.row_offset = torch.from_numpy(off).to(device)
         self.halo_idx = None if self.halo_idx_host is None else torch.from_numpy(self.halo_idx_host).to(device)
+        self.recv_order_host = None if self.halo_idx_host is None else B.adaqp_plan_recv_order(self.halo_idx_host)
+        self.recv_order = None if self.recv_order_host is None else torch.from_numpy(self.recv_order_host).to(device)
+
+
+def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
+    """Uploads a [n, dim] fp32 matrix into rows whose pitch is a whole number of 128-byte lines (the layout
+    the kernels are built for) and returns the [n, dim] view; the padding columns are zero."""
+    n, dim = a.shape
+    ld = (dim + 31) // 32 * 32 if pad else dim
+    buf = torch.zeros((n, ld), dtype=torch.float32, device=device)
+    view = buf[:, :dim]
+    view.copy_(torch.from_numpy(a))
+    return view
 
 
 class LayerStep:
-    def __init__(self, p: Partition, device="cuda:0", seed: int = 0):
+    def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True):
         self.p = p
         self.device = torch.device(device)
         dev = self.device
@@ -78,8 +91,8 @@ class LayerStep:
         self.rowptr = torch.from_numpy(p.rowptr).to(dev)
         self.col = torch.from_numpy(p.col).to(dev)
         self.val = torch.from_numpy(p.val).to(dev)
-        self.feat = torch.from_numpy(p.feat).to(dev)
-        self.out = torch.zeros((p.n_rows, cfg.dim), dtype=torch.float32, device=dev)
+        self.feat = line_padded(p.feat, dev, pad)
+        self.out = line_padded(np.zeros((p.n_rows, cfg.dim), dtype=np.float32), dev, pad)
         self.plan = SendPlan(cfg.dim, p.send_idx, p.bits, p.peer_of_slot, cfg.n_peers,
                              None if self.backward else p.halo_idx, dev)
         n = self.plan.n
@@ -116,6 +129,7 @@ class LayerStep:
         d.send_idx_dev, d.bits_dev = pl.send_idx.data_ptr(), pl.bits.data_ptr()
         d.row_offset_dev = pl.row_offset.data_ptr()
         d.halo_idx_dev = None if pl.halo_idx is None else pl.halo_idx.data_ptr()
+        d.recv_order_dev = None if pl.recv_order is None else pl.recv_order.data_ptr()
         d.n_send, d.seed = pl.n, self.seed
         d.packed_dev, d.params_dev = self.packed.data_ptr(), self.params.data_ptr()
         d.recv_packed_dev, d.recv_params_dev = self.recv_packed.data_ptr(), self.recv_params.data_ptr()

@@ -42,7 +42,12 @@ def _gpu_quantize(feat_np, dim, send_idx, bits, off, seed, packed_bytes, fill=0x
     return packed.cpu().numpy(), params.cpu().numpy()
 
 
-def _codec_case(oracle, feat_np, dim, send_idx, bits, peer, n_peers, seed, halo_rows=None):
+def _padded_cols(dim, ld):
+    """Columns a line-padded output row gets zero-filled (torch allocations are at least 256-byte aligned)."""
+    return min(ld, (dim + 31) // 32 * 32) if ld % 32 == 0 else dim
+
+
+def _codec_case(oracle, feat_np, dim, send_idx, bits, peer, n_peers, seed, halo_rows=None, use_order=False):
     """Quantise on both sides, compare bytes and params; de-quantise on both sides, compare floats."""
     perm, off, pbp = oracle.plan_layout(dim, bits, peer, n_peers)
     perm_g, off_g, pbp_g = B.adaqp_plan_layout(dim, bits, peer, n_peers)
@@ -64,23 +69,29 @@ def _codec_case(oracle, feat_np, dim, send_idx, bits, peer, n_peers, seed, halo_
                                 else np.random.default_rng(seed).permutation(n_rows)[:n], dtype=np.int32)
     want = np.full((n_rows, ld), np.float32(-123.5))
     oracle.unpack_dequant(want_packed, want_params, s_bits, off, halo, dim, want)
+    want[halo, dim:_padded_cols(dim, ld)] = 0.0            # whole-line writes zero the row padding
     got = torch.full((n_rows, ld), -123.5, dtype=torch.float32, device=DEV)
+    order = torch.from_numpy(B.adaqp_plan_recv_order(halo)).to(DEV) if use_order else None
     B.adaqp_unpack_dequant(torch.from_numpy(want_packed if nbytes else np.zeros(4, np.uint8)).to(DEV),
                            torch.from_numpy(want_params if n else np.zeros((1, 2), np.float32)).to(DEV),
                            torch.from_numpy(s_bits).to(DEV), torch.from_numpy(off).to(DEV),
-                           torch.from_numpy(halo).to(DEV), dim, got)
+                           torch.from_numpy(halo).to(DEV), dim, got, order=order)
     torch.cuda.synchronize()
     assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32)), "de-quantised rows differ"
 
 
 @pytest.mark.parametrize("dim,ld", [(128, 128), (602, 602), (256, 256), (300, 300), (300, 301), (7, 7), (1, 1),
                                     (8, 12), (9, 9), (33, 40), (63, 63), (64, 64), (65, 66), (1000, 1000),
-                                    (4096, 4096), (4100, 4100), (5000, 5001)])
+                                    (4096, 4096), (4100, 4100), (5000, 5001),
+                                    # line-padded pitches: whole-line reads and writes, ragged last vector
+                                    (602, 608), (300, 320), (7, 32), (33, 64), (1, 32), (130, 160), (1000, 1024),
+                                    (250, 256), (2047, 2048), (2049, 2080), (4100, 4128), (602, 640), (602, 604)])
 def test_codec_shapes(oracle, dim, ld):
     _say(f"codec dim={dim} ld={ld}")
     rng = np.random.default_rng(dim * 7 + ld)
     n_rows, n = 300, 211                       # several blocks of rows and a ragged last block
     feat = rng.standard_normal((n_rows, ld), dtype=np.float32)
+    feat[:, dim:] = np.float32(1e30)           # padding must never enter min / max
     feat[3] = 1.25                                                    # constant row
     feat[4, : dim // 2] = 0.0
     feat[5] = np.maximum(feat[5], 0)
@@ -89,7 +100,7 @@ def test_codec_shapes(oracle, dim, ld):
     send[:8] = np.arange(8)
     bits = rng.choice(np.array([2, 4, 8], dtype=np.uint8), size=n)
     peer = np.sort(rng.integers(0, 3, size=n)).astype(np.int32)
-    _codec_case(oracle, feat, dim, send, bits, peer, 3, seed=dim)
+    _codec_case(oracle, feat, dim, send, bits, peer, 3, seed=dim, use_order=(dim % 2 == 0))
 
 
 @pytest.mark.parametrize("b", [2, 4, 8])
@@ -172,14 +183,17 @@ def _gpu_spmm(rowptr, col, val, rb, re, H, dim, nnz_range=-1, out_fill=7.0, ldo=
 
 def _check_spmm(oracle, rowptr, col, val, rb, re, H, dim, **kw):
     got = _gpu_spmm(rowptr, col, val, rb, re, H, dim, **kw)
-    want, mag = oracle.spmm_csr(rowptr, col, val, rb, re, H, dim)
+    Hc = np.ascontiguousarray(H[:, :dim]) if H.shape[1] != dim else H
+    want, mag = oracle.spmm_csr(rowptr, col, val, rb, re, Hc, dim)
     err = np.abs(got[rb:re, :dim].astype(np.float64) - want)
     tol = SPMM_RTOL * mag + 1e-30
     worst = float((err / tol).max()) if err.size else 0.0
     assert worst <= 1.0, f"worst error {worst:.3f} x tolerance"
     assert np.all(got[:rb] == 7.0) and np.all(got[re:] == 7.0), "rows outside the range were written"
-    if got.shape[1] > dim:
-        assert np.all(got[:, dim:] == 7.0), "columns past dim were written"
+    ldo, ldh = got.shape[1], H.shape[1]
+    zero_to = _padded_cols(dim, ldo) if (ldo % 32 == 0 and ldh % 32 == 0) else dim
+    assert np.all(got[rb:re, dim:zero_to] == 0.0), "row padding of written rows must be zero"
+    assert np.all(got[:, zero_to:] == 7.0), "columns past the padded row were written"
     return got
 
 
@@ -197,7 +211,9 @@ def _random_graph(rng, n_rows, n_cols, degs):
 
 
 @pytest.mark.parametrize("dim,ldh", [(128, 128), (602, 602), (256, 256), (300, 300), (1, 1), (7, 9), (66, 66),
-                                     (130, 132), (2048, 2048), (2052, 2052), (515, 515)])
+                                     (130, 132), (2048, 2048), (2052, 2052), (515, 515),
+                                     # line-padded pitches (H padding holds NaN: it must never reach the output)
+                                     (602, 608), (300, 320), (7, 32), (250, 256), (2049, 2080), (129, 160)])
 def test_spmm_shapes(oracle, dim, ldh):
     _say(f"spmm dim={dim} ldh={ldh}")
     rng = np.random.default_rng(dim)
@@ -208,11 +224,13 @@ def test_spmm_shapes(oracle, dim, ldh):
     degs[500:520] = 0                                                  # a run of empty rows
     degs[699] = 300                                                    # heavy last row
     rowptr, col, val = _random_graph(rng, n_rows, n_cols, degs)
-    H = np.zeros((n_cols, ldh), dtype=np.float32)
+    H = np.full((n_cols, ldh), np.nan, dtype=np.float32)
     H[:, :dim] = rng.standard_normal((n_cols, dim), dtype=np.float32)
-    _check_spmm(oracle, rowptr, col, val, 0, n_rows, H, dim)
-    _check_spmm(oracle, rowptr, col, val, 9, 12, H, dim, nnz_range="exact")
-    _check_spmm(oracle, rowptr, col, val, 495, 700, H, dim, nnz_range="exact")
+    ldo = ldh if ldh % 32 == 0 else dim
+    _check_spmm(oracle, rowptr, col, val, 0, n_rows, H, dim, ldo=ldo)
+    _check_spmm(oracle, rowptr, col, val, 9, 12, H, dim, nnz_range="exact", ldo=ldo)
+    _check_spmm(oracle, rowptr, col, val, 495, 700, H, dim, nnz_range="exact", ldo=ldo)
+    _check_spmm(oracle, rowptr, col, val, 0, n_rows, H, dim, ldo=dim + 3)            # unpadded output
 
 
 def test_spmm_degenerate(oracle):

@@ -66,15 +66,15 @@ def test_argument_errors_are_caught_before_any_launch():
     one = ctypes.c_void_p(256)          # a non-NULL, aligned dummy; never dereferenced on these paths
     # zero counts are successful no-ops
     assert L.adaqp_quantize_pack(None, 0, 8, 8, None, None, None, 0, 0, None, 0, None, None) == B.OK
-    assert L.adaqp_unpack_dequant(None, 0, None, None, None, None, 0, 8, None, 0, 8, None) == B.OK
+    assert L.adaqp_unpack_dequant(None, 0, None, None, None, None, None, 0, 8, None, 0, 8, None) == B.OK
     assert L.adaqp_spmm_csr(None, None, None, 0, 3, 3, -1, None, 0, 8, 8, None, 8, None, 0, None) == B.OK
     # bad shapes
     assert L.adaqp_quantize_pack(one, 4, 7, 8, one, one, one, 1, 0, one, 64, one, None) == B.EINVAL   # ld < dim
     assert L.adaqp_quantize_pack(one, 4, 8, 0, one, one, one, 1, 0, one, 64, one, None) == B.EINVAL   # dim 0
     assert L.adaqp_quantize_pack(one, 4, 8, 8, one, one, one, -1, 0, one, 64, one, None) == B.EINVAL  # n < 0
     assert L.adaqp_quantize_pack(None, 4, 8, 8, one, one, one, 1, 0, one, 64, one, None) == B.EINVAL  # NULL
-    assert L.adaqp_unpack_dequant(one, 64, one, one, one, one, 1, 8, None, 4, 8, None) == B.EINVAL
-    assert L.adaqp_unpack_dequant(one, 64, one, one, one, one, 1, 8, one, 4, 4, None) == B.EINVAL     # ld < dim
+    assert L.adaqp_unpack_dequant(one, 64, one, one, one, one, None, 1, 8, None, 4, 8, None) == B.EINVAL
+    assert L.adaqp_unpack_dequant(one, 64, one, one, one, one, None, 1, 8, one, 4, 4, None) == B.EINVAL  # ld < dim
     assert L.adaqp_spmm_csr(one, one, one, 5, 2, 1, -1, one, 4, 8, 8, one, 8, one, 1 << 20, None) == B.EINVAL
     assert L.adaqp_spmm_csr(one, one, one, 5, 0, 2, -1, one, 4, 4, 8, one, 8, one, 1 << 20, None) == B.EINVAL
     # workspace too small
@@ -92,3 +92,15 @@ def test_workspace_query():
     assert small % 256 == 0 and big % 256 == 0 and 0 < small < big < (1 << 30)
     with pytest.raises(B.AdaqpError):
         B.adaqp_spmm_workspace_bytes(-1, 0, 8)
+
+
+def test_plan_recv_order():
+    rng = np.random.default_rng(3)
+    halo = rng.permutation(5000)[:700].astype(np.int32) + 100
+    order = B.adaqp_plan_recv_order(halo)
+    assert order.dtype == np.int32 and sorted(order.tolist()) == list(range(700))
+    assert np.all(np.diff(halo[order]) > 0)
+    assert np.array_equal(order, np.argsort(halo, kind="stable"))
+    assert B.adaqp_plan_recv_order(np.zeros(0, np.int32)).size == 0
+    # ties keep slot order
+    assert B.adaqp_plan_recv_order(np.array([5, 1, 5, 1], np.int32)).tolist() == [1, 3, 0, 2]
