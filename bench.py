@@ -32,9 +32,18 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c1", help="c0..c4 (c1 is the configuration the metric is quoted on)")
-    ap.add_argument("--schedule", default="isolated", choices=["serial", "isolated", "free"])
+    ap.add_argument("--schedule", default="serial", choices=["serial", "isolated", "free"],
+                    help="schedule of the timed steps.  The three give the same time on one GPU (the aggregation "
+                         "fills the device, and there is no transfer to hide); serial is the default because its "
+                         "kernels never overlap, so per-kernel durations of a rocprofv3 trace are meaningful")
     ap.add_argument("--kernel-reps", type=int, default=20, help="launches per kernel in the breakdown")
+    ap.add_argument("--all-schedules", action="store_true",
+                    help="also time 3 steps of the other two schedules (their aggregation launches overlap, which "
+                         "inflates per-kernel durations in a trace of the same run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch a plain elementwise kernel of known size (reads and writes 256 MiB): the "
+                         "reference dispatch that scales the FETCH_SIZE / WRITE_SIZE counters of a --pmc run")
     ap.add_argument("--cpu-budget-s", type=float, default=15.0)
     return ap.parse_args()
 
@@ -129,7 +138,7 @@ def main():
     import numpy as np
     import torch
     from paper_2306_01381_amd import binding as B
-    from paper_2306_01381_amd.layer import LayerStep
+    from paper_2306_01381_amd.layer import LayerStep, line_padded
     from paper_2306_01381_amd.synth import config_by_name, make_partition
 
     if not torch.cuda.is_available():
@@ -159,7 +168,10 @@ def main():
     ms_per_step = timed_steps(sched[args.schedule], args.steps, args.warmup)
     other = {}
     for name, s in sched.items():
-        other[name] = ms_per_step if name == args.schedule else timed_steps(s, max(3, args.steps // 4), 1)
+        if name == args.schedule:
+            other[name] = ms_per_step
+        elif args.all_schedules:
+            other[name] = timed_steps(s, 3, 1)
 
     # ---- per-kernel breakdown: the same launches the step makes, each alone on its stream, HIP events ----
     dim = cfg.dim
@@ -168,12 +180,13 @@ def main():
     qbytes, dbytes = codec_bytes(dim, pl.bits_host, B)
     st = L.stream_msg
     kernels = {}
-    # cold protocol for the codec: rotate over enough copies of the operand that it cannot sit in the 256 MB
-    # last-level cache between launches
+    # cold protocol for the codec: rotate over enough copies of the operand that the rows a launch touches
+    # (n_send rows, not the whole matrix) cannot survive in the 256 MB last-level cache until their next use
     src = L.out if cfg.backward else L.feat
-    n_copies = int(min(8, max(2, -(-640_000_000 // (src.numel() * 4)))))
-    srcs = [src] + [src.clone() for _ in range(n_copies - 1)]
-    packs = [L.packed] + [torch.empty_like(L.packed) for _ in range(n_copies - 1)]
+    touched = max(1, pl.n * dim * 4)
+    n_copies = int(min(12, max(2, -(-640_000_000 // touched))))
+    srcs = [src] + [line_padded(src.cpu().numpy(), dev) for _ in range(n_copies - 1)]
+    packs = [L.packed] + [torch.zeros_like(L.packed) for _ in range(n_copies - 1)]
     pars = [L.params] + [torch.empty_like(L.params) for _ in range(n_copies - 1)]
     torch.cuda.synchronize()
 
@@ -192,10 +205,12 @@ def main():
     if not cfg.backward:
         def d_cold(i):
             k = i % n_copies
-            B.adaqp_unpack_dequant(packs[k], pars[k], pl.bits, pl.row_offset, pl.halo_idx, dim, srcs[k], stream=st)
+            B.adaqp_unpack_dequant(packs[k], pars[k], pl.bits, pl.row_offset, pl.halo_idx, dim, srcs[k],
+                                   order=(pl.recv_order if L.use_recv_order else None), stream=st)
 
         def d_warm(i):
-            B.adaqp_unpack_dequant(packs[0], pars[0], pl.bits, pl.row_offset, pl.halo_idx, dim, srcs[0], stream=st)
+            B.adaqp_unpack_dequant(packs[0], pars[0], pl.bits, pl.row_offset, pl.halo_idx, dim, srcs[0],
+                                   order=(pl.recv_order if L.use_recv_order else None), stream=st)
 
         for k in range(n_copies):           # every copy holds valid packed data
             q_cold(k)
@@ -248,6 +263,18 @@ def main():
         "roofline": roofline,
         "setup_s": {"generate": t_gen},
     }
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):
+        # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/README.md)
+        entry = json.load(open(traffic_file)).get(cfg.name, {}).get("spmm_merge_kernel")
+        if entry:
+            roofline["traffic"] = entry
+    if args.calibrate:
+        a_ = torch.zeros(1 << 26, dtype=torch.float32, device=dev)
+        b_ = torch.empty_like(a_)
+        for _ in range(3):
+            torch.add(a_, 1.0, out=b_)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(p, pl, args.cpu_budget_s)
     print(json.dumps(result))

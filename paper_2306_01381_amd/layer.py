@@ -80,7 +80,7 @@ def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
 
 
 class LayerStep:
-    def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True):
+    def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False):
         self.p = p
         self.device = torch.device(device)
         dev = self.device
@@ -88,6 +88,7 @@ class LayerStep:
         self.dim = cfg.dim
         self.backward = bool(cfg.backward)
         self.seed = seed
+        self.use_recv_order = use_recv_order
         self.rowptr = torch.from_numpy(p.rowptr).to(dev)
         self.col = torch.from_numpy(p.col).to(dev)
         self.val = torch.from_numpy(p.val).to(dev)
@@ -129,7 +130,7 @@ class LayerStep:
         d.send_idx_dev, d.bits_dev = pl.send_idx.data_ptr(), pl.bits.data_ptr()
         d.row_offset_dev = pl.row_offset.data_ptr()
         d.halo_idx_dev = None if pl.halo_idx is None else pl.halo_idx.data_ptr()
-        d.recv_order_dev = None if pl.recv_order is None else pl.recv_order.data_ptr()
+        d.recv_order_dev = pl.recv_order.data_ptr() if (self.use_recv_order and pl.recv_order is not None) else None
         d.n_send, d.seed = pl.n, self.seed
         d.packed_dev, d.params_dev = self.packed.data_ptr(), self.params.data_ptr()
         d.recv_packed_dev, d.recv_params_dev = self.recv_packed.data_ptr(), self.recv_params.data_ptr()
