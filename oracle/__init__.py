@@ -42,7 +42,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_row_stride.restype = i64
         L.oracle_plan_layout.argtypes = [i64, i32, vp, vp, i32, vp, vp, vp]
         L.oracle_plan_layout.restype = ctypes.c_int
-        L.oracle_quantize_pack.argtypes = [vp, i64, i32, vp, vp, vp, i64, u64, vp, vp, vp]
+        L.oracle_quantize_pack.argtypes = [vp, i64, i32, vp, vp, vp, i64, u64, i64, vp, vp, vp]
         L.oracle_quantize_pack.restype = ctypes.c_int
         L.oracle_unpack_dequant.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, i64, vp]
         L.oracle_unpack_dequant.restype = ctypes.c_int
@@ -92,8 +92,10 @@ def plan_layout(dim: int, bits: np.ndarray, peer_of_slot: np.ndarray, n_peers: i
 
 
 def quantize_pack(feat: np.ndarray, dim: int, send_idx: np.ndarray, bits: np.ndarray,
-                  row_offset: np.ndarray, seed: int, packed_bytes: int, want_codes: bool = False):
-    """Returns (packed uint8[packed_bytes], params float32[n,2], codes uint8[n,dim] or None)."""
+                  row_offset: np.ndarray, seed: int, packed_bytes: int, want_codes: bool = False,
+                  slot_base: int = 0):
+    """Returns (packed uint8[packed_bytes], params float32[n,2], codes uint8[n,dim] or None).
+    slot_base is the slot number of entry 0 (the random stream is keyed by slot number)."""
     assert feat.dtype == np.float32 and feat.ndim == 2 and feat.flags.c_contiguous
     send_idx = _chk(send_idx, np.int32)
     bits = _chk(bits, np.uint8)
@@ -103,7 +105,7 @@ def quantize_pack(feat: np.ndarray, dim: int, send_idx: np.ndarray, bits: np.nda
     params = np.zeros((n, 2), dtype=np.float32)
     codes = np.zeros((n, dim), dtype=np.uint8) if want_codes else None
     rc = lib().oracle_quantize_pack(_p(feat), feat.shape[1], dim, _p(send_idx), _p(bits), _p(row_offset),
-                                    n, seed, _p(packed), _p(params), _p(codes))
+                                    n, seed, slot_base, _p(packed), _p(params), _p(codes))
     if rc != 0:
         raise ValueError(f"oracle_quantize_pack failed: {rc}")
     return packed, params, codes

@@ -122,10 +122,12 @@ int oracle_plan_layout(int64_t n, int32_t dim, const uint8_t *bits, const int32_
 
 /* ------------------------------------------------------------------------------------------------------ */
 /* Quantise + pack (Eq. 4 with R1-R6).  codes_out (optional, [n_send * dim]) receives the unpacked codes.   */
+/* slot_base: slot number of the first entry of the arrays (the random stream is keyed by slot number), so  */
+/* that any contiguous run of slots - or a single one - can be computed on its own.                        */
 /* ------------------------------------------------------------------------------------------------------ */
 int oracle_quantize_pack(const float *feat, int64_t ld, int32_t dim,
                          const int32_t *send_idx, const uint8_t *bits, const int64_t *row_offset,
-                         int64_t n_send, uint64_t seed,
+                         int64_t n_send, uint64_t seed, int64_t slot_base,
                          uint8_t *packed, float *params, uint8_t *codes_out)
 {
     if (n_send < 0 || dim <= 0 || ld < dim) return ORACLE_EINVAL;
@@ -156,7 +158,7 @@ int oracle_quantize_pack(const float *feat, int64_t ld, int32_t dim,
             float x = (h[j] - Z) * inv;            /* position on the integer grid, >= 0 */
             if (x > levels) x = levels;            /* R1: the top element may overshoot by an ulp */
             const uint32_t t = (uint32_t)(x * 65536.0f);          /* R2: 16.16 fixed point, truncated */
-            const uint32_t code = (t + oracle_rand16(seed, (uint64_t)s, (uint32_t)j)) >> 16;
+            const uint32_t code = (t + oracle_rand16(seed, (uint64_t)(slot_base + s), (uint32_t)j)) >> 16;
             if (codes_out) codes_out[s * (int64_t)dim + j] = (uint8_t)code;
             const int64_t bit = (int64_t)j * b;    /* R5 */
             row[bit >> 3] |= (uint8_t)(code << (bit & 7));

@@ -249,3 +249,20 @@ def test_gather_uses_send_idx_and_ld(oracle):
     # slots 0 and 2 carry the same node but are different messages: independent randomness is allowed,
     # identical parameters up to the width are required
     assert params[0, 0] == params[2, 0]
+
+
+def test_slot_base_selects_the_same_random_stream(oracle):
+    """A run of slots computed on its own (slot_base) gives the bytes it has inside the full computation."""
+    rng = np.random.default_rng(12)
+    rows = rng.standard_normal((9, 70), dtype=np.float32)
+    for b in WIDTHS:
+        packed, params, codes, off = _single_width(oracle, rows, b, seed=77)
+        stride = oracle.row_stride(70, b)
+        for s in (0, 4, 8):
+            p1, q1, c1 = oracle.quantize_pack(rows, 70, np.array([s], np.int32), np.array([b], np.uint8),
+                                              np.array([0], np.int64), 77, stride, want_codes=True, slot_base=s)
+            assert np.array_equal(p1, packed[off[s]: off[s] + stride])
+            assert np.array_equal(c1[0], codes[s]) and np.array_equal(q1[0], params[s])
+        p0, _, _ = oracle.quantize_pack(rows, 70, np.array([4], np.int32), np.array([b], np.uint8),
+                                        np.array([0], np.int64), 77, stride, slot_base=0)
+        assert not np.array_equal(p0, packed[off[4]: off[4] + stride])      # slot 0's stream differs from slot 4's
