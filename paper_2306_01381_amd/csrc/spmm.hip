@@ -62,6 +62,16 @@ __device__ __forceinline__ void store_vec(float *p, const float *src)
     if constexpr (VW == 4) { *reinterpret_cast<V *>(p) = make_float4(src[0], src[1], src[2], src[3]); }
 }
 
+// Same, marked non-temporal: output rows are written once and not read again by this kernel.
+template <int VW>
+__device__ __forceinline__ void store_vec_streaming(float *p, const float *src)
+{
+    typedef float vec_t __attribute__((ext_vector_type(VW)));
+    vec_t v;
+    for (int k = 0; k < VW; ++k) v[k] = src[k];
+    __builtin_nontemporal_store(v, reinterpret_cast<vec_t *>(p));
+}
+
 __device__ __forceinline__ int64_t clamp64(int64_t v, int64_t lo, int64_t hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 __device__ __forceinline__ int32_t uniform_i32(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -159,7 +169,7 @@ __global__ __launch_bounds__(kBlock) void spmm_merge_kernel(const SpmmArgs a)
         }
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            if (v < NV - 1 || last_ok) store_vec<VW>(o + (v * kWave + lane) * VW, acc[v]);
+            if (v < NV - 1 || last_ok) store_vec_streaming<VW>(o + (v * kWave + lane) * VW, acc[v]);
 #pragma unroll
             for (int k = 0; k < VW; ++k) acc[v][k] = 0.0f;
         }
@@ -180,8 +190,8 @@ __global__ __launch_bounds__(kBlock) void spmm_merge_kernel(const SpmmArgs a)
         int32_t my_col = 0;
         float my_val = 0.0f;
         if (lane < nb) {
-            my_col = colp[j + lane];
-            my_val = valp[j + lane];
+            my_col = __builtin_nontemporal_load(colp + j + lane);     // streamed once: keep the caches for H
+            my_val = __builtin_nontemporal_load(valp + j + lane);
             if (my_col < 0 || my_col >= a.n_cols) { my_col = 0; my_val = 0.0f; }   // out-of-range entry: skipped
         }
         for (int32_t e = 0; e < nb; e += U) {
