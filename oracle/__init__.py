@@ -46,6 +46,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_quantize_pack.restype = ctypes.c_int
         L.oracle_unpack_dequant.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, i64, vp]
         L.oracle_unpack_dequant.restype = ctypes.c_int
+        L.oracle_unpack_dequant_add.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, i64]
+        L.oracle_unpack_dequant_add.restype = ctypes.c_int
         L.oracle_spmm_csr.argtypes = [vp, vp, vp, i64, i64, vp, i64, i32, vp, i64, vp, vp]
         L.oracle_spmm_csr.restype = ctypes.c_int
         _lib = L
@@ -127,6 +129,21 @@ def unpack_dequant(packed: np.ndarray, params: np.ndarray, bits: np.ndarray, row
     if rc != 0:
         raise ValueError(f"oracle_unpack_dequant failed: {rc}")
     return codes
+
+
+def unpack_dequant_add(packed: np.ndarray, params: np.ndarray, bits: np.ndarray, row_offset: np.ndarray,
+                       dst_idx: np.ndarray, dim: int, grad: np.ndarray) -> None:
+    """grad[dst_idx[t]] += de-quantised slot t, slots applied in order (in place)."""
+    assert grad.dtype == np.float32 and grad.ndim == 2 and grad.flags.c_contiguous
+    packed = _chk(packed, np.uint8)
+    params = _chk(params, np.float32)
+    bits = _chk(bits, np.uint8)
+    row_offset = _chk(row_offset, np.int64)
+    dst_idx = _chk(dst_idx, np.int32)
+    rc = lib().oracle_unpack_dequant_add(_p(packed), _p(params), _p(bits), _p(row_offset), _p(dst_idx),
+                                         dst_idx.shape[0], dim, _p(grad), grad.shape[1])
+    if rc != 0:
+        raise ValueError(f"oracle_unpack_dequant_add failed: {rc}")
 
 
 def spmm_csr(rowptr: np.ndarray, col: np.ndarray, val: np.ndarray, row_begin: int, row_end: int,

@@ -14,6 +14,7 @@
  *   sub-byte merging   Sec. 5 "Implementation": 2- and 4-bit codes are merged into a byte stream; messages are
  *                      grouped by bit-width, each group quantised at one width, groups concatenated per peer
  *   aggregation        Sec. 2.1 Eq. 3 (inner sum):  out_v = sum over u in {v} U N(v) of alpha(u,v) * h_u
+ *   backward receive   Sec. 3.1: received gradient messages are de-quantised (Eq. 5) and added to the owner's rows
  *
  * Readings taken where the paper is silent (each one is restated next to the code that uses it):
  *   R1  one fp32 division per row gives inv = (2^b-1)/(max-min); elements are multiplied by inv and clamped
@@ -187,6 +188,34 @@ int oracle_unpack_dequant(const uint8_t *packed, const float *params,
             if (codes_out) codes_out[t * (int64_t)dim + j] = (uint8_t)code;
             const float scaled = (float)code * S;  /* Eq. 5, two roundings: product, then sum */
             h[j] = scaled + Z;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------------------------ */
+/* Backward receive (Sec. 3.1: in the backward pass the embedding gradients of remote neighbours travel back   */
+/* to the owner of the node, quantised the same way; the owner de-quantises them, Eq. 5, and adds them to the   */
+/* gradient row of that node).  Slots are applied in slot order: grad[dst[t]] = grad[dst[t]] + h^_t, one fp32   */
+/* addition per element and slot, so a node that hears from several peers accumulates them in slot order.      */
+/* ------------------------------------------------------------------------------------------------------ */
+int oracle_unpack_dequant_add(const uint8_t *packed, const float *params,
+                              const uint8_t *bits, const int64_t *row_offset, const int32_t *dst_idx,
+                              int64_t n_recv, int32_t dim, float *grad, int64_t ld)
+{
+    if (n_recv < 0 || dim <= 0 || ld < dim) return ORACLE_EINVAL;
+    for (int64_t t = 0; t < n_recv; ++t) {
+        const int b = bits[t];
+        if (b != 2 && b != 4 && b != 8) return ORACLE_EBITS;
+        const float Z = params[2 * t + 0], S = params[2 * t + 1];
+        const uint8_t *row = packed + row_offset[t];
+        float *g = grad + (int64_t)dst_idx[t] * ld;
+        for (int32_t j = 0; j < dim; ++j) {
+            const int64_t bit = (int64_t)j * b;
+            const uint32_t code = ((uint32_t)row[bit >> 3] >> (bit & 7)) & ((1u << b) - 1u);
+            const float scaled = (float)code * S;
+            const float value = scaled + Z;        /* Eq. 5 */
+            g[j] = g[j] + value;
         }
     }
     return ORACLE_OK;

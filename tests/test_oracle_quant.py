@@ -266,3 +266,48 @@ def test_slot_base_selects_the_same_random_stream(oracle):
         p0, _, _ = oracle.quantize_pack(rows, 70, np.array([4], np.int32), np.array([b], np.uint8),
                                         np.array([0], np.int64), 77, stride, slot_base=0)
         assert not np.array_equal(p0, packed[off[4]: off[4] + stride])      # slot 0's stream differs from slot 4's
+
+
+# ------------------------------------------------------------------------------------------------------
+# backward receive: de-quantise and add (Sec. 3.1)
+# ------------------------------------------------------------------------------------------------------
+
+def test_dequant_add_closed_form_and_order(oracle):
+    # a row 0..3 at 2 bits de-quantises to itself; two such messages onto a row of ones give 1 + 2 j
+    row = np.arange(4, dtype=np.float32)[None, :]
+    packed, params, codes, off = _single_width(oracle, np.repeat(row, 2, 0), 2, seed=3)
+    grad = np.ones((3, 6), dtype=np.float32)
+    oracle.unpack_dequant_add(packed, params, np.full(2, 2, np.uint8), off, np.array([1, 1], np.int32), 4, grad)
+    assert np.array_equal(grad[1, :4], 1 + 2 * np.arange(4)) and np.all(grad[1, 4:] == 1)
+    assert np.all(grad[0] == 1) and np.all(grad[2] == 1)
+
+
+def test_dequant_add_equals_dequant_on_zero_rows_and_is_sequential(oracle):
+    rng = np.random.default_rng(31)
+    dim = 37
+    rows = rng.standard_normal((6, dim), dtype=np.float32)
+    for b in WIDTHS:
+        packed, params, codes, off = _single_width(oracle, rows, b, seed=b)
+        bits = np.full(6, b, np.uint8)
+        plain = np.zeros((6, dim), dtype=np.float32)
+        oracle.unpack_dequant(packed, params, bits, off, np.arange(6, dtype=np.int32), dim, plain)
+        # distinct destinations starting from +0: identical to the plain de-quantisation
+        grad = np.zeros((6, dim), dtype=np.float32)
+        oracle.unpack_dequant_add(packed, params, bits, off, np.arange(6, dtype=np.int32), dim, grad)
+        assert np.array_equal(grad, plain + np.float32(0))
+        # all six onto one row: the fp32 sum taken in slot order
+        grad = np.full((2, dim), np.float32(0.5))
+        oracle.unpack_dequant_add(packed, params, bits, off, np.zeros(6, np.int32), dim, grad)
+        want = np.full(dim, np.float32(0.5))
+        for t in range(6):
+            want = want + plain[t]
+        assert np.array_equal(grad[0], want) and np.all(grad[1] == 0.5)
+        # a different slot order gives the sum in that order (fp32 addition is not associative)
+        perm = np.array([5, 3, 1, 0, 2, 4])
+        grad2 = np.full((1, dim), np.float32(0.5))
+        oracle.unpack_dequant_add(packed, params[perm], bits, off[perm], np.zeros(6, np.int32), dim, grad2)
+        want2 = np.full(dim, np.float32(0.5))
+        for t in perm:
+            want2 = want2 + plain[t]
+        assert np.array_equal(grad2[0], want2)
+        assert np.allclose(grad2[0], grad[0], rtol=1e-5, atol=1e-6)
