@@ -219,6 +219,29 @@ def main():
         tw = event_time_ms(st, d_warm, reps)
         kernels["unpack_dequant"] = {"ms": t, "GBps": dbytes / t / 1e6, "frac_hbm": dbytes / t / 1e6 / HBM_PEAK_GBPS,
                                      "ms_warm": tw, "GBps_warm": dbytes / tw / 1e6, "bytes": dbytes}
+    else:
+        # backward receive: the received buffer is de-quantised and added to the local rows it targets
+        n_seg = pl.seg_ptr.shape[0] - 1
+        strides = {b: B.adaqp_row_stride(dim, b) for b in (2, 4, 8)}
+        abytes = int(sum(strides[int(b)] for b in pl.bits_host)) + pl.n * (8 + 17) + n_seg * (8 * dim + 8)
+
+        def a_cold(i):
+            k = i % n_copies
+            B.adaqp_unpack_dequant_add(packs[k], pars[k], pl.bits, pl.row_offset, pl.halo_idx, pl.seg_order,
+                                       pl.seg_ptr, dim, srcs[k], stream=st)
+
+        def a_warm(i):
+            B.adaqp_unpack_dequant_add(packs[0], pars[0], pl.bits, pl.row_offset, pl.halo_idx, pl.seg_order,
+                                       pl.seg_ptr, dim, srcs[0], stream=st)
+
+        for k in range(n_copies):
+            q_cold(k)
+        st.synchronize()
+        t = event_time_ms(st, a_cold, reps)
+        tw = event_time_ms(st, a_warm, reps)
+        kernels["unpack_dequant_add"] = {"ms": t, "GBps": abytes / t / 1e6, "frac_hbm": abytes / t / 1e6 / HBM_PEAK_GBPS,
+                                         "ms_warm": tw, "GBps_warm": abytes / tw / 1e6, "bytes": abytes,
+                                         "rows": n_seg, "messages": pl.n}
     del srcs, packs, pars
 
     (ob, oe), (db_, de) = p.overlap_rows, p.dependent_rows

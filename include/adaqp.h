@@ -128,6 +128,30 @@ int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_bytes, const 
                          float *feat_dev, int64_t n_feat_rows, int64_t ld, void *stream);
 
 /* ---------------------------------------------------------------------------------------------------- */
+/* Backward receive: Sec. 3.1 - in the backward pass the gradients of remote neighbours travel back to the */
+/* node's owner quantised the same way; the owner de-quantises them (Eq. 5) and adds them to its own rows. */
+/* ---------------------------------------------------------------------------------------------------- */
+
+/* Host only: groups n received slots by destination row.  order_out[n] lists the slots sorted by
+ * (dst_idx, slot); seg_ptr_out[n + 1] delimits runs of equal destination: segment g is
+ * order_out[seg_ptr_out[g] .. seg_ptr_out[g+1]); *n_seg_out = number of segments (distinct rows).
+ * Errors: EINVAL, ESIZE (n > 2^31 - 1). */
+int adaqp_plan_recv_segments(int64_t n, const int32_t *dst_idx_host, int32_t *order_out, int64_t *seg_ptr_out,
+                             int64_t *n_seg_out);
+
+/* For every segment, in slot order:  grad[dst, j] = grad[dst, j] + ((float)code_j * S + Z)  - one fp32
+ * addition per slot and element, so a node that hears from several peers accumulates them in slot order and
+ * the result does not depend on the launch.  Per-slot arrays (params, bits, row_offset, dst_idx) are in slot
+ * order as for adaqp_unpack_dequant; seg_order_dev / seg_ptr_dev come from adaqp_plan_recv_segments.
+ * Only columns [0, dim) of the destination rows change (padding columns keep their contents).
+ * Out-of-range slots are skipped.  Errors: EINVAL, ESIZE, EHIP. */
+int adaqp_unpack_dequant_add(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
+                             const uint8_t *bits_dev, const int64_t *row_offset_dev, const int32_t *dst_idx_dev,
+                             int64_t n_recv, const int32_t *seg_order_dev, const int64_t *seg_ptr_dev,
+                             int64_t n_seg, int32_t dim, float *grad_dev, int64_t n_grad_rows, int64_t ld,
+                             void *stream);
+
+/* ---------------------------------------------------------------------------------------------------- */
 /* Aggregation: Sec. 2.1 Eq. 3, inner sum.  The coefficients alpha(u,v) are the CSR values; the self term  */
 /* is an explicit entry.                                                                                   */
 /* ---------------------------------------------------------------------------------------------------- */
@@ -174,7 +198,9 @@ typedef enum adaqp_direction {
                            the de-quantisation */
     ADAQP_BACKWARD = 1  /* the CSR is the transposed graph and `feat` holds the output gradients: aggregate
                            dependent_rows (halo rows of A^T dY) first, quantise + pack them from `out`,
-                           loop back; overlap_rows (local rows) on stream_agg */
+                           loop back; overlap_rows (local rows) on stream_agg; then, if receive segments are
+                           given, de-quantise the received buffer and add it to rows of `out` (halo_idx_dev =
+                           destination rows), after both aggregations have finished */
 } adaqp_direction;
 
 typedef struct adaqp_layer_desc {
@@ -199,6 +225,9 @@ typedef struct adaqp_layer_desc {
     const int64_t *row_offset_dev;
     const int32_t *halo_idx_dev;    /* forward only: destination rows of the received slots */
     const int32_t *recv_order_dev;  /* forward only, optional: adaqp_plan_recv_order of halo_idx */
+    const int32_t *recv_seg_order_dev;  /* backward only, optional: adaqp_plan_recv_segments of halo_idx */
+    const int64_t *recv_seg_ptr_dev;
+    int64_t n_recv_seg;
     int64_t n_send;
     uint64_t seed;
     uint8_t *packed_dev;   float *params_dev;           /* send buffers */

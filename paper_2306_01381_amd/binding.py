@@ -45,6 +45,7 @@ class LayerDesc(ctypes.Structure):
         ("out_dev", _vp), ("ldo", _i64),
         ("send_idx_dev", _vp), ("bits_dev", _vp), ("row_offset_dev", _vp), ("halo_idx_dev", _vp),
         ("recv_order_dev", _vp),
+        ("recv_seg_order_dev", _vp), ("recv_seg_ptr_dev", _vp), ("n_recv_seg", _i64),
         ("n_send", _i64), ("seed", _u64),
         ("packed_dev", _vp), ("params_dev", _vp), ("recv_packed_dev", _vp), ("recv_params_dev", _vp),
         ("packed_bytes", _i64),
@@ -65,6 +66,9 @@ _SIGNATURES = {
     "adaqp_quantize_pack": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _u64, _vp, _i64, _vp, _vp]),
     "adaqp_plan_recv_order": (ctypes.c_int, [_i64, _vp, _vp]),
     "adaqp_unpack_dequant": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i64, _vp]),
+    "adaqp_plan_recv_segments": (ctypes.c_int, [_i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
+    "adaqp_unpack_dequant_add": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _i32,
+                                                _vp, _i64, _i64, _vp]),
     "adaqp_spmm_workspace_bytes": (ctypes.c_int, [_i64, _i64, _i32, ctypes.POINTER(_i64)]),
     "adaqp_spmm_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
                                       _vp, _i64, _vp, _i64, _vp]),
@@ -173,6 +177,33 @@ def adaqp_unpack_dequant(packed: torch.Tensor, params: torch.Tensor, bits: torch
                                       n, dim, fp, n_rows, ld,
                                       _stream(stream)),
            "adaqp_unpack_dequant")
+
+
+def adaqp_plan_recv_segments(dst_idx_host: np.ndarray):
+    """Host-only.  Returns (order int32[n], seg_ptr int64[n_seg + 1])."""
+    dst = np.ascontiguousarray(dst_idx_host, dtype=np.int32)
+    n = dst.shape[0]
+    order = np.zeros(n, dtype=np.int32)
+    seg_ptr = np.zeros(n + 1, dtype=np.int64)
+    n_seg = _i64(0)
+    _check(lib().adaqp_plan_recv_segments(n, dst.ctypes.data, order.ctypes.data, seg_ptr.ctypes.data,
+                                          ctypes.byref(n_seg)), "adaqp_plan_recv_segments")
+    return order, seg_ptr[: n_seg.value + 1].copy()
+
+
+def adaqp_unpack_dequant_add(packed: torch.Tensor, params: torch.Tensor, bits: torch.Tensor,
+                             row_offset: torch.Tensor, dst_idx: torch.Tensor, seg_order: torch.Tensor,
+                             seg_ptr: torch.Tensor, dim: int, grad: torch.Tensor,
+                             stream: Optional[torch.cuda.Stream] = None) -> None:
+    gp, n_rows, ld = _matrix(grad, "grad")
+    _check(lib().adaqp_unpack_dequant_add(_dev(packed, torch.uint8, "packed"), packed.numel(),
+                                          _dev(params, torch.float32, "params"), _dev(bits, torch.uint8, "bits"),
+                                          _dev(row_offset, torch.int64, "row_offset"),
+                                          _dev(dst_idx, torch.int32, "dst_idx"), dst_idx.shape[0],
+                                          _dev(seg_order, torch.int32, "seg_order"),
+                                          _dev(seg_ptr, torch.int64, "seg_ptr"), seg_ptr.shape[0] - 1,
+                                          dim, gp, n_rows, ld, _stream(stream)),
+           "adaqp_unpack_dequant_add")
 
 
 def adaqp_spmm_workspace_bytes(n_rows: int, nnz: int, dim: int) -> int:

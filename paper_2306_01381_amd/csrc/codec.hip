@@ -482,6 +482,112 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_long_kernel(const Dequa
     for (int32_t c = a.dim + lane; c < a.write_dim; c += kWave) h[c] = 0.0f;           // row padding
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Backward receive: one wave per destination row.  The slots that target the row (a node hears from every peer
+// that holds it as a halo node) were grouped on the host; the wave stages their index entries in lanes, loads
+// the row, adds the de-quantised messages in slot order (one fp32 addition per slot and element: the order is
+// part of the result) and stores the row once.  Rows wider than 64*VW*4 columns are walked in column chunks.
+// ---------------------------------------------------------------------------------------------------------
+struct DequantAddArgs {
+    const uint8_t *packed;
+    int64_t packed_bytes;
+    const float *params;
+    const uint8_t *bits;
+    const int64_t *row_offset;
+    const int32_t *dst_idx;
+    int64_t n_recv;
+    const int32_t *seg_order;
+    const int64_t *seg_ptr;
+    int64_t n_seg;
+    int32_t dim;
+    float *grad;
+    int64_t n_grad_rows, ld;
+};
+
+template <int VW>
+__global__ __launch_bounds__(kBlock) void unpack_dequant_add_kernel(const DequantAddArgs a)
+{
+    constexpr int NV = 4;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t g = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);             // wave-uniform
+    if (g >= a.n_seg) return;
+    int64_t k0 = a.seg_ptr[g], k1 = a.seg_ptr[g + 1];
+    k0 = k0 < 0 ? 0 : (k0 > a.n_recv ? a.n_recv : k0);
+    k1 = k1 < k0 ? k0 : (k1 > a.n_recv ? a.n_recv : k1);
+    if (k0 >= k1) return;
+    const int32_t t_first = a.seg_order[k0];
+    if (t_first < 0 || t_first >= a.n_recv) return;
+    const int32_t r = a.dst_idx[t_first];                       // the segment's destination row
+    if (r < 0 || r >= a.n_grad_rows) return;
+    float *row = a.grad + (int64_t)r * a.ld;
+
+    for (int32_t c0 = 0; c0 < a.dim; c0 += kWave * VW * NV) {
+        float acc[NV][VW];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int32_t c = c0 + (v * kWave + lane) * VW;
+#pragma unroll
+            for (int q = 0; q < VW; ++q) acc[v][q] = 0.0f;
+            if (c < a.dim) load_vec<VW>(row + c, acc[v]);
+        }
+        for (int64_t win = k0; win < k1; win += kWave) {
+            // index entries of up to 64 slots of the segment: lane j <-> slot win + j ("skip" = width 0)
+            const int32_t n_win = (int32_t)(k1 - win < kWave ? k1 - win : kWave);
+            int32_t my_b = 0;
+            int64_t my_off = 0;
+            float my_z = 0.0f, my_s = 0.0f;
+            if (lane < n_win) {
+                const int32_t t = a.seg_order[win + lane];
+                if (t >= 0 && t < a.n_recv && a.dst_idx[t] == r) {
+                    my_b = a.bits[t];
+                    my_off = a.row_offset[t];
+                    const float2 zs = *reinterpret_cast<const float2 *>(a.params + 2 * (int64_t)t);
+                    my_z = zs.x;
+                    my_s = zs.y;
+                    const int64_t stride = 4 * (((int64_t)a.dim * my_b + 31) >> 5);
+                    const bool ok = (my_b == 2 || my_b == 4 || my_b == 8) && my_off >= 0 && (my_off & 3) == 0 &&
+                                    my_off + stride <= a.packed_bytes;
+                    if (!ok) my_b = 0;
+                }
+            }
+            for (int32_t j = 0; j < n_win; ++j) {
+                const int32_t b = __builtin_amdgcn_readlane(my_b, j);
+                if (b == 0) continue;
+                const int64_t off = readlane_i64(my_off, j);
+                const float Z = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_z), j));
+                const float S = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_s), j));
+                const uint32_t *words = reinterpret_cast<const uint32_t *>(a.packed + off);
+                const uint32_t last_word = (uint32_t)(((int64_t)a.dim * b - 1) >> 5);
+                const uint32_t mask = (1u << b) - 1u;
+                uint32_t w[NV];
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const uint32_t bit = (uint32_t)(c0 + (v * kWave + lane) * VW) * (uint32_t)b;
+                    const uint32_t idx = (bit >> 5) < last_word ? (bit >> 5) : last_word;
+                    w[v] = words[idx];
+                }
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const uint32_t bit = (uint32_t)(c0 + (v * kWave + lane) * VW) * (uint32_t)b;
+                    const uint32_t word = w[v] >> (bit & 31u);
+#pragma unroll
+                    for (int q = 0; q < VW; ++q) {
+                        const uint32_t code = (word >> (q * b)) & mask;
+                        const float scaled = (float)code * S;      // Eq. 5: product rounded, then sum rounded
+                        const float value = scaled + Z;
+                        acc[v][q] = acc[v][q] + value;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int32_t c = c0 + (v * kWave + lane) * VW;
+            if (c < a.dim) store_vec<VW>(row + c, acc[v]);
+        }
+    }
+}
+
 constexpr int kMaxGpl = 8;
 
 // Largest vector width (floats) such that every row start is naturally aligned.  `whole_vectors`: the width
@@ -655,6 +761,52 @@ extern "C" int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_by
     if (vw_long == 4) hipLaunchKernelGGL(unpack_dequant_long_kernel<4>, grid, dim3(kBlock), 0, st, a);
     else if (vw_long == 2) hipLaunchKernelGGL(unpack_dequant_long_kernel<2>, grid, dim3(kBlock), 0, st, a);
     else hipLaunchKernelGGL(unpack_dequant_long_kernel<1>, grid, dim3(kBlock), 0, st, a);
+    ADAQP_HIP_TRY(hipGetLastError());
+    return ADAQP_OK;
+}
+
+extern "C" int adaqp_unpack_dequant_add(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
+                                        const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                                        const int32_t *dst_idx_dev, int64_t n_recv, const int32_t *seg_order_dev,
+                                        const int64_t *seg_ptr_dev, int64_t n_seg, int32_t dim, float *grad_dev,
+                                        int64_t n_grad_rows, int64_t ld, void *stream)
+{
+    if (n_recv < 0 || n_seg < 0 || dim <= 0 || ld < dim || n_grad_rows < 0 || packed_bytes < 0) return ADAQP_EINVAL;
+    if (n_recv == 0 || n_seg == 0) return ADAQP_OK;
+    if (!packed_dev || !params_dev || !bits_dev || !row_offset_dev || !dst_idx_dev || !seg_order_dev ||
+        !seg_ptr_dev || !grad_dev)
+        return ADAQP_EINVAL;
+    if (n_grad_rows == 0 || n_seg > n_recv) return ADAQP_EINVAL;
+    if (!aligned_to(grad_dev, 4) || !aligned_to(params_dev, 8) || !aligned_to(packed_dev, 4) ||
+        !aligned_to(dst_idx_dev, 4) || !aligned_to(row_offset_dev, 8) || !aligned_to(seg_order_dev, 4) ||
+        !aligned_to(seg_ptr_dev, 8))
+        return ADAQP_EINVAL;
+    if (n_recv > INT32_MAX) return ADAQP_ESIZE;
+    if (packed_bytes < 4) return ADAQP_OK;          // no row fits: every slot would be skipped
+    const int64_t blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > INT32_MAX) return ADAQP_ESIZE;
+
+    DequantAddArgs a;
+    a.packed = packed_dev;
+    a.packed_bytes = packed_bytes;
+    a.params = params_dev;
+    a.bits = bits_dev;
+    a.row_offset = row_offset_dev;
+    a.dst_idx = dst_idx_dev;
+    a.n_recv = n_recv;
+    a.seg_order = seg_order_dev;
+    a.seg_ptr = seg_ptr_dev;
+    a.n_seg = n_seg;
+    a.dim = dim;
+    a.grad = grad_dev;
+    a.n_grad_rows = n_grad_rows;
+    a.ld = ld;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid((unsigned)blocks);
+    const int vw = vector_width(grad_dev, ld, dim, true);
+    if (vw == 4) hipLaunchKernelGGL(unpack_dequant_add_kernel<4>, grid, dim3(kBlock), 0, st, a);
+    else if (vw == 2) hipLaunchKernelGGL(unpack_dequant_add_kernel<2>, grid, dim3(kBlock), 0, st, a);
+    else hipLaunchKernelGGL(unpack_dequant_add_kernel<1>, grid, dim3(kBlock), 0, st, a);
     ADAQP_HIP_TRY(hipGetLastError());
     return ADAQP_OK;
 }

@@ -102,6 +102,27 @@ extern "C" int adaqp_plan_recv_order(int64_t n, const int32_t *halo_idx_host, in
     return ADAQP_OK;
 }
 
+extern "C" int adaqp_plan_recv_segments(int64_t n, const int32_t *dst_idx_host, int32_t *order_out,
+                                        int64_t *seg_ptr_out, int64_t *n_seg_out)
+{
+    if (n < 0 || !n_seg_out || !seg_ptr_out) return ADAQP_EINVAL;
+    *n_seg_out = 0;
+    seg_ptr_out[0] = 0;
+    if (n == 0) return ADAQP_OK;
+    if (!dst_idx_host || !order_out) return ADAQP_EINVAL;
+    if (n > INT32_MAX) return ADAQP_ESIZE;
+    for (int64_t i = 0; i < n; ++i) order_out[i] = (int32_t)i;
+    std::stable_sort(order_out, order_out + n,
+                     [dst_idx_host](int32_t x, int32_t y) { return dst_idx_host[x] < dst_idx_host[y]; });
+    int64_t n_seg = 0;
+    for (int64_t k = 0; k < n; ++k) {
+        if (k == 0 || dst_idx_host[order_out[k]] != dst_idx_host[order_out[k - 1]]) seg_ptr_out[n_seg++] = k;
+    }
+    seg_ptr_out[n_seg] = n;
+    *n_seg_out = n_seg;
+    return ADAQP_OK;
+}
+
 namespace {
 
 int check_desc(const adaqp_layer_desc *d)
@@ -237,6 +258,16 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
         }
         ADAQP_STEP(loop_back(d, msg));
         if (d->schedule == ADAQP_SERIAL) ADAQP_STEP(aggregate(d, true, msg));
+        if (d->n_recv_seg > 0 && d->recv_seg_order_dev && d->recv_seg_ptr_dev && d->halo_idx_dev) {
+            // the received gradients are added to rows that the local aggregation also writes: join first
+            ADAQP_STEP(join_now());
+            ADAQP_STEP(adaqp_unpack_dequant_add(d->recv_packed_dev, d->packed_bytes, d->recv_params_dev, d->bits_dev,
+                                                d->row_offset_dev, d->halo_idx_dev, d->n_send,
+                                                d->recv_seg_order_dev, d->recv_seg_ptr_dev, d->n_recv_seg, d->dim,
+                                                d->out_dev,
+                                                d->dependent_end > d->overlap_end ? d->dependent_end : d->overlap_end,
+                                                d->ldo, msg));
+        }
     }
     ADAQP_STEP(join_now());
 #undef ADAQP_STEP

@@ -51,7 +51,7 @@ class SendPlan:
     """Sorted slot order and byte offsets of one direction's messages (host arrays + device copies)."""
 
     def __init__(self, dim: int, send_idx: np.ndarray, bits: np.ndarray, peer_of_slot: np.ndarray,
-                 n_peers: int, halo_idx: Optional[np.ndarray], device):
+                 n_peers: int, halo_idx: Optional[np.ndarray], device, add_segments: bool = False):
         perm, off, pbp = B.adaqp_plan_layout(dim, bits, peer_of_slot, n_peers)
         self.perm, self.row_offset_host, self.peer_byte_ptr = perm, off, pbp
         self.send_idx_host = np.ascontiguousarray(send_idx[perm], dtype=np.int32)
@@ -66,6 +66,13 @@ class SendPlan:
         self.halo_idx = None if self.halo_idx_host is None else torch.from_numpy(self.halo_idx_host).to(device)
         self.recv_order_host = None if self.halo_idx_host is None else B.adaqp_plan_recv_order(self.halo_idx_host)
         self.recv_order = None if self.recv_order_host is None else torch.from_numpy(self.recv_order_host).to(device)
+        # backward receive: slots grouped by destination row
+        self.seg_order = self.seg_ptr = None
+        if add_segments and self.halo_idx_host is not None:
+            order, seg_ptr = B.adaqp_plan_recv_segments(self.halo_idx_host)
+            self.seg_order_host, self.seg_ptr_host = order, seg_ptr
+            self.seg_order = torch.from_numpy(order).to(device)
+            self.seg_ptr = torch.from_numpy(seg_ptr).to(device)
 
 
 def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
@@ -80,7 +87,8 @@ def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
 
 
 class LayerStep:
-    def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False):
+    def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False,
+                 backward_receive: bool = True):
         self.p = p
         self.device = torch.device(device)
         dev = self.device
@@ -89,13 +97,14 @@ class LayerStep:
         self.backward = bool(cfg.backward)
         self.seed = seed
         self.use_recv_order = use_recv_order
+        self.backward_receive = backward_receive
         self.rowptr = torch.from_numpy(p.rowptr).to(dev)
         self.col = torch.from_numpy(p.col).to(dev)
         self.val = torch.from_numpy(p.val).to(dev)
         self.feat = line_padded(p.feat, dev, pad)
         self.out = line_padded(np.zeros((p.n_rows, cfg.dim), dtype=np.float32), dev, pad)
-        self.plan = SendPlan(cfg.dim, p.send_idx, p.bits, p.peer_of_slot, cfg.n_peers,
-                             None if self.backward else p.halo_idx, dev)
+        self.plan = SendPlan(cfg.dim, p.send_idx, p.bits, p.peer_of_slot, cfg.n_peers, p.halo_idx, dev,
+                             add_segments=self.backward)
         n = self.plan.n
         nbytes = max(self.plan.packed_bytes, 4)
         self.packed = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
@@ -130,7 +139,11 @@ class LayerStep:
         d.send_idx_dev, d.bits_dev = pl.send_idx.data_ptr(), pl.bits.data_ptr()
         d.row_offset_dev = pl.row_offset.data_ptr()
         d.halo_idx_dev = None if pl.halo_idx is None else pl.halo_idx.data_ptr()
-        d.recv_order_dev = pl.recv_order.data_ptr() if (self.use_recv_order and pl.recv_order is not None) else None
+        d.recv_order_dev = pl.recv_order.data_ptr() if (self.use_recv_order and pl.recv_order is not None
+                                                        and not self.backward) else None
+        if self.backward and self.backward_receive and pl.seg_order is not None:
+            d.recv_seg_order_dev, d.recv_seg_ptr_dev = pl.seg_order.data_ptr(), pl.seg_ptr.data_ptr()
+            d.n_recv_seg = pl.seg_ptr.shape[0] - 1
         d.n_send, d.seed = pl.n, self.seed
         d.packed_dev, d.params_dev = self.packed.data_ptr(), self.params.data_ptr()
         d.recv_packed_dev, d.recv_params_dev = self.recv_packed.data_ptr(), self.recv_params.data_ptr()

@@ -84,7 +84,8 @@ class Partition:
     send_idx: np.ndarray        # int32 [n_send]  row of the send matrix for each slot, slots sorted by peer
     peer_of_slot: np.ndarray    # int32 [n_send]  non-decreasing
     bits: np.ndarray            # uint8 [n_send]  in {2, 4, 8}
-    halo_idx: np.ndarray        # int32 [n_send]  destination row of each received slot (forward only)
+    halo_idx: np.ndarray        # int32 [n_send]  destination row of each received slot (forward: halo rows, each
+                                # once; backward: local marginal rows the received gradients are added to)
     meta: dict = field(default_factory=dict)
 
     @property
@@ -236,8 +237,13 @@ def make_partition(cfg: PartitionConfig, seed: Optional[int] = None) -> Partitio
     sq = np.add.reduceat(np.square(t_val.astype(np.float64)), t_rowptr[:-1].clip(max=t_val.shape[0] - 1))
     sq[np.diff(t_rowptr) == 0] = 0.0
     bits = _bits(rng, cfg.bits, cfg.n_send, sq[send_rows])
+    # loop-back stand-in for what the peers send back: every received slot carries the gradient of one of this
+    # partition's marginal nodes; a peer names a node at most once, different peers may name the same node
+    n_marg = n_local - n_central
+    dst = np.concatenate([n_central + rng.permutation(n_marg)[:c] if c <= n_marg
+                          else n_central + rng.integers(0, n_marg, size=c) for c in cnt]).astype(np.int32)
     return Partition(cfg, t_rowptr, t_col, t_val, n_cols, n_local,
                      overlap_rows=(0, n_local), dependent_rows=(n_local, n_cols),
                      n_central=n_central, feat=dy,
                      send_idx=send_rows.astype(np.int32), peer_of_slot=peer_of_slot, bits=bits,
-                     halo_idx=np.zeros(0, dtype=np.int32), meta={"direction": "backward"})
+                     halo_idx=dst, meta={"direction": "backward"})

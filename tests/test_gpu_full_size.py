@@ -62,7 +62,7 @@ def test_full_size_layer_step(oracle, name):
     _say(f"full size {name}: generating")
     p = make_partition(cfg)
     dim = cfg.dim
-    L = LayerStep(p, "cuda:0", seed=SEED)
+    L = LayerStep(p, "cuda:0", seed=SEED, backward_receive=False)
     if not cfg.backward:
         L.feat[cfg.n_local: cfg.n_local + cfg.n_send] = float("nan")     # must be produced by the step
     L.out.fill_(float("nan"))
@@ -122,3 +122,44 @@ def test_full_size_layer_step(oracle, name):
         sent = p.feat[pl.send_idx_host]
         got = feat_after[pl.halo_idx_host]
         assert np.all(np.abs(got - sent) <= params[:, 1:2] * (1 + 1e-4) + 1e-30)
+
+
+def test_full_size_backward_receive(oracle):
+    """c4 with the receive side on: the received gradients are added to the local rows in slot order."""
+    cfg = CONFIGS["c4"]
+    _say("full size c4 backward receive: generating")
+    p = make_partition(cfg)
+    dim = cfg.dim
+    base = LayerStep(p, "cuda:0", seed=SEED, backward_receive=False)
+    base.run(B.SERIAL)
+    base.synchronize()
+    out0 = base.out.cpu().numpy()
+    packed = base.recv_packed.cpu().numpy()[: base.plan.packed_bytes]
+    params = base.recv_params.cpu().numpy()[: base.plan.n]
+    del base
+    L = LayerStep(p, "cuda:0", seed=SEED)
+    L.out.fill_(float("nan"))
+    L.run(B.ISOLATED)
+    L.synchronize()
+    out1 = L.out.cpu().numpy()
+    pl = L.plan
+    assert np.array_equal(L.recv_packed.cpu().numpy()[: pl.packed_bytes], packed)
+    dst = pl.halo_idx_host
+    touched = np.zeros(p.n_rows, dtype=bool)
+    touched[dst] = True
+    assert np.array_equal(out1[~touched].view(np.uint32), out0[~touched].view(np.uint32))
+    rng = np.random.default_rng(5)
+    counts = np.bincount(dst, minlength=p.n_rows)
+    rows = set(rng.choice(np.nonzero(touched)[0], size=200, replace=False).tolist())
+    rows |= set(np.argsort(counts)[-5:].tolist())                     # the rows that hear from the most peers
+    for r in sorted(rows):
+        slots = np.nonzero(dst == r)[0]                                # ascending = slot order
+        want = np.ascontiguousarray(out0[r: r + 1].copy())
+        for s in slots:
+            b = int(pl.bits_host[s])
+            stride = B.adaqp_row_stride(dim, b)
+            off = int(pl.row_offset_host[s])
+            oracle.unpack_dequant_add(packed[off: off + stride], params[s: s + 1], pl.bits_host[s: s + 1],
+                                      np.zeros(1, np.int64), np.zeros(1, np.int32), dim, want)
+        assert np.array_equal(out1[r].view(np.uint32), want[0].view(np.uint32)), f"row {r}: {len(slots)} messages"
+    _say(f"full size c4 backward receive: {len(rows)} rows ok, up to {counts.max()} messages per row")

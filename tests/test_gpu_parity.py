@@ -163,6 +163,39 @@ def test_codec_skips_invalid_slots_and_empty_input(oracle):
 
 
 # ------------------------------------------------------------------------------------------------------
+# backward receive: de-quantise and add
+# ------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dim,ld", [(128, 128), (602, 608), (602, 602), (256, 256), (300, 320), (7, 7), (1, 1),
+                                    (33, 40), (1100, 1120), (2500, 2500)])
+def test_dequant_add(oracle, dim, ld):
+    _say(f"dequant add dim={dim} ld={ld}")
+    rng = np.random.default_rng(dim + ld)
+    n_rows, n = 180, 400
+    src = rng.standard_normal((n, dim), dtype=np.float32) * np.float32(1e-3)
+    bits = rng.choice(np.array([2, 4, 8], dtype=np.uint8), size=n)
+    peer = np.sort(rng.integers(0, 7, size=n)).astype(np.int32)
+    perm, off, pbp = oracle.plan_layout(dim, bits, peer, 7)
+    s_bits = np.ascontiguousarray(bits[perm])
+    packed, params, _ = oracle.quantize_pack(src, dim, perm.astype(np.int32), s_bits, off, 5, int(pbp[-1]))
+    dst = rng.integers(60, 160, size=n).astype(np.int32)          # ~4 messages per row, rows 0..59 untouched
+    dst[:3] = [-1, n_rows, 61]                                      # two out-of-range destinations: skipped
+    order, seg_ptr = B.adaqp_plan_recv_segments(dst)
+    grad0 = rng.standard_normal((n_rows, ld), dtype=np.float32)
+    want = grad0.copy()
+    ok = (dst >= 0) & (dst < n_rows)
+    idx = np.nonzero(ok)[0]
+    oracle.unpack_dequant_add(packed, params[idx], s_bits[idx], off[idx], dst[idx], dim, want)
+    got = torch.from_numpy(grad0).to(DEV)
+    B.adaqp_unpack_dequant_add(torch.from_numpy(packed).to(DEV), torch.from_numpy(params).to(DEV),
+                               torch.from_numpy(s_bits).to(DEV), torch.from_numpy(off).to(DEV),
+                               torch.from_numpy(dst).to(DEV), torch.from_numpy(order).to(DEV),
+                               torch.from_numpy(seg_ptr).to(DEV), dim, got)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+# ------------------------------------------------------------------------------------------------------
 # aggregation
 # ------------------------------------------------------------------------------------------------------
 
@@ -319,7 +352,7 @@ def test_layer_step_matches_oracle_in_every_schedule(oracle, name):
     packed_w, params_w, feat_w, out64, mag = _oracle_layer(oracle, p, seed)
     results = []
     for schedule in (B.SERIAL, B.ISOLATED, B.FREE):
-        L = LayerStep(p, DEV, seed=seed)
+        L = LayerStep(p, DEV, seed=seed, backward_receive=False)
         if not cfg.backward:
             # poison what the step must produce, so that a missing dependency shows as NaN
             L.feat[cfg.n_local: cfg.n_local + cfg.n_send] = float("nan")
@@ -344,7 +377,7 @@ def test_layer_step_matches_oracle_in_every_schedule(oracle, name):
     if cfg.backward:
         # the oracle quantises the GPU's own fp32 aggregate: the codes depend on every bit of the input, and
         # the aggregate is only specified to a tolerance
-        L = LayerStep(p, DEV, seed=seed)
+        L = LayerStep(p, DEV, seed=seed, backward_receive=False)
         L.run(B.SERIAL)
         L.synchronize()
         g = L.out.cpu().numpy()
@@ -352,3 +385,16 @@ def test_layer_step_matches_oracle_in_every_schedule(oracle, name):
                                                            L.plan.row_offset_host, seed, L.plan.packed_bytes)
         assert np.array_equal(L.recv_packed.cpu().numpy()[: L.plan.packed_bytes], want_packed)
         assert np.array_equal(L.recv_params.cpu().numpy()[: L.plan.n].view(np.uint32), want_params.view(np.uint32))
+        # with the receive side switched on, the received gradients are added to the local rows in slot order:
+        # the oracle adds the same received bytes to the aggregate computed above
+        want_out = np.ascontiguousarray(g.copy())
+        oracle.unpack_dequant_add(want_packed, want_params, L.plan.bits_host, L.plan.row_offset_host,
+                                  L.plan.halo_idx_host, cfg.dim, want_out)
+        assert not np.array_equal(want_out, g)
+        for schedule in (B.SERIAL, B.ISOLATED, B.FREE):
+            L2 = LayerStep(p, DEV, seed=seed)
+            L2.out.fill_(float("nan"))
+            L2.run(schedule)
+            L2.synchronize()
+            assert np.array_equal(L2.out.cpu().numpy().view(np.uint32), want_out.view(np.uint32)), \
+                f"schedule {schedule}: backward receive differs"

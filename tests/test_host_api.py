@@ -104,3 +104,21 @@ def test_plan_recv_order():
     assert B.adaqp_plan_recv_order(np.zeros(0, np.int32)).size == 0
     # ties keep slot order
     assert B.adaqp_plan_recv_order(np.array([5, 1, 5, 1], np.int32)).tolist() == [1, 3, 0, 2]
+
+
+def test_plan_recv_segments():
+    dst = np.array([7, 3, 7, 9, 3, 3], dtype=np.int32)
+    order, seg_ptr = B.adaqp_plan_recv_segments(dst)
+    assert order.tolist() == [1, 4, 5, 0, 2, 3]              # by destination, slot order inside
+    assert seg_ptr.tolist() == [0, 3, 5, 6]
+    order, seg_ptr = B.adaqp_plan_recv_segments(np.zeros(0, np.int32))
+    assert order.size == 0 and seg_ptr.tolist() == [0]
+    rng = np.random.default_rng(8)
+    dst = rng.integers(0, 300, size=2000).astype(np.int32)
+    order, seg_ptr = B.adaqp_plan_recv_segments(dst)
+    assert sorted(order.tolist()) == list(range(2000))
+    assert np.all(np.diff(dst[order]) >= 0)
+    assert len(seg_ptr) - 1 == len(np.unique(dst))
+    for g in range(len(seg_ptr) - 1):
+        seg = order[seg_ptr[g]: seg_ptr[g + 1]]
+        assert len(set(dst[seg].tolist())) == 1 and np.all(np.diff(seg) > 0)

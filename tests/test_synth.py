@@ -53,3 +53,9 @@ def test_backward_partition_is_the_transpose():
     assert p.overlap_rows == (0, 900) and p.dependent_rows == (900, 1600)
     assert set(np.unique(p.bits)) == {2, 4, 8}
     assert np.abs(p.feat).max() < 0.01
+    # received gradients target this partition's marginal rows; a peer names a row once, peers may overlap
+    assert p.halo_idx.shape == (500,) and p.halo_idx.min() >= p.n_central and p.halo_idx.max() < 900
+    for peer in range(cfg.n_peers):
+        rows = p.halo_idx[p.peer_of_slot == peer]
+        assert len(set(rows.tolist())) == len(rows)
+    assert len(set(p.halo_idx.tolist())) < 500
