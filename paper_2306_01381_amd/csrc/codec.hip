@@ -504,10 +504,10 @@ struct DequantAddArgs {
     int64_t n_grad_rows, ld;
 };
 
-template <int VW>
+template <int VW, int NV>       // NV: vectors per lane and column chunk
 __global__ __launch_bounds__(kBlock) void unpack_dequant_add_kernel(const DequantAddArgs a)
 {
-    constexpr int NV = 4;
+    constexpr int G = 4;        // slots whose packed words are requested together
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t g = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);             // wave-uniform
     if (g >= a.n_seg) return;
@@ -515,67 +515,82 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_add_kernel(const Dequan
     k0 = k0 < 0 ? 0 : (k0 > a.n_recv ? a.n_recv : k0);
     k1 = k1 < k0 ? k0 : (k1 > a.n_recv ? a.n_recv : k1);
     if (k0 >= k1) return;
-    const int32_t t_first = a.seg_order[k0];
-    if (t_first < 0 || t_first >= a.n_recv) return;
-    const int32_t r = a.dst_idx[t_first];                       // the segment's destination row
-    if (r < 0 || r >= a.n_grad_rows) return;
-    float *row = a.grad + (int64_t)r * a.ld;
 
+    int32_t r = -1;             // the segment's destination row: that of its first slot
+    float *row = nullptr;
     for (int32_t c0 = 0; c0 < a.dim; c0 += kWave * VW * NV) {
         float acc[NV][VW];
-#pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const int32_t c = c0 + (v * kWave + lane) * VW;
-#pragma unroll
-            for (int q = 0; q < VW; ++q) acc[v][q] = 0.0f;
-            if (c < a.dim) load_vec<VW>(row + c, acc[v]);
-        }
         for (int64_t win = k0; win < k1; win += kWave) {
             // index entries of up to 64 slots of the segment: lane j <-> slot win + j ("skip" = width 0)
             const int32_t n_win = (int32_t)(k1 - win < kWave ? k1 - win : kWave);
-            int32_t my_b = 0;
+            int32_t my_t = -1, my_dst = -1, my_b = 0;
             int64_t my_off = 0;
             float my_z = 0.0f, my_s = 0.0f;
             if (lane < n_win) {
-                const int32_t t = a.seg_order[win + lane];
-                if (t >= 0 && t < a.n_recv && a.dst_idx[t] == r) {
-                    my_b = a.bits[t];
-                    my_off = a.row_offset[t];
-                    const float2 zs = *reinterpret_cast<const float2 *>(a.params + 2 * (int64_t)t);
+                my_t = a.seg_order[win + lane];
+                if (my_t >= 0 && my_t < a.n_recv) {
+                    my_dst = a.dst_idx[my_t];
+                    my_b = a.bits[my_t];
+                    my_off = a.row_offset[my_t];
+                    const float2 zs = *reinterpret_cast<const float2 *>(a.params + 2 * (int64_t)my_t);
                     my_z = zs.x;
                     my_s = zs.y;
-                    const int64_t stride = 4 * (((int64_t)a.dim * my_b + 31) >> 5);
-                    const bool ok = (my_b == 2 || my_b == 4 || my_b == 8) && my_off >= 0 && (my_off & 3) == 0 &&
-                                    my_off + stride <= a.packed_bytes;
-                    if (!ok) my_b = 0;
                 }
             }
-            for (int32_t j = 0; j < n_win; ++j) {
-                const int32_t b = __builtin_amdgcn_readlane(my_b, j);
-                if (b == 0) continue;
-                const int64_t off = readlane_i64(my_off, j);
-                const float Z = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_z), j));
-                const float S = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_s), j));
-                const uint32_t *words = reinterpret_cast<const uint32_t *>(a.packed + off);
-                const uint32_t last_word = (uint32_t)(((int64_t)a.dim * b - 1) >> 5);
-                const uint32_t mask = (1u << b) - 1u;
-                uint32_t w[NV];
+            if (win == k0) {
+                r = __builtin_amdgcn_readlane(my_dst, 0);
+                if (r < 0 || r >= a.n_grad_rows) return;
+                row = a.grad + (int64_t)r * a.ld;
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
-                    const uint32_t bit = (uint32_t)(c0 + (v * kWave + lane) * VW) * (uint32_t)b;
-                    const uint32_t idx = (bit >> 5) < last_word ? (bit >> 5) : last_word;
-                    w[v] = words[idx];
+                    const int32_t c = c0 + (v * kWave + lane) * VW;
+#pragma unroll
+                    for (int q = 0; q < VW; ++q) acc[v][q] = 0.0f;
+                    if (c < a.dim) load_vec<VW>(row + c, acc[v]);
+                }
+            }
+            {
+                const int64_t stride = 4 * (((int64_t)a.dim * my_b + 31) >> 5);
+                const bool ok = my_dst == r && (my_b == 2 || my_b == 4 || my_b == 8) && my_off >= 0 &&
+                                (my_off & 3) == 0 && my_off + stride <= a.packed_bytes;
+                if (!ok) { my_b = 0; my_off = 0; }
+            }
+            for (int32_t j0 = 0; j0 < n_win; j0 += G) {
+                // packed words of up to G slots in one run of loads (a skipped slot reads the buffer's first word)
+                uint32_t w[G][NV];
+#pragma unroll
+                for (int u = 0; u < G; ++u) {
+                    const int32_t j = j0 + u < n_win ? j0 + u : n_win - 1;
+                    const int32_t b = __builtin_amdgcn_readlane(my_b, j);
+                    const int64_t off = readlane_i64(my_off, j);
+                    const uint32_t *words = reinterpret_cast<const uint32_t *>(a.packed + off);
+                    const uint32_t last_word = b ? (uint32_t)(((int64_t)a.dim * b - 1) >> 5) : 0u;
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) {
+                        const uint32_t bit = (uint32_t)(c0 + (v * kWave + lane) * VW) * (uint32_t)b;
+                        const uint32_t idx = (bit >> 5) < last_word ? (bit >> 5) : last_word;
+                        w[u][v] = words[idx];
+                    }
                 }
 #pragma unroll
-                for (int v = 0; v < NV; ++v) {
-                    const uint32_t bit = (uint32_t)(c0 + (v * kWave + lane) * VW) * (uint32_t)b;
-                    const uint32_t word = w[v] >> (bit & 31u);
+                for (int u = 0; u < G; ++u) {
+                    if (j0 + u >= n_win) break;
+                    const int32_t b = __builtin_amdgcn_readlane(my_b, j0 + u);
+                    if (b == 0) continue;
+                    const float Z = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_z), j0 + u));
+                    const float S = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_s), j0 + u));
+                    const uint32_t mask = (1u << b) - 1u;
 #pragma unroll
-                    for (int q = 0; q < VW; ++q) {
-                        const uint32_t code = (word >> (q * b)) & mask;
-                        const float scaled = (float)code * S;      // Eq. 5: product rounded, then sum rounded
-                        const float value = scaled + Z;
-                        acc[v][q] = acc[v][q] + value;
+                    for (int v = 0; v < NV; ++v) {
+                        const uint32_t bit = (uint32_t)(c0 + (v * kWave + lane) * VW) * (uint32_t)b;
+                        const uint32_t word = w[u][v] >> (bit & 31u);
+#pragma unroll
+                        for (int q = 0; q < VW; ++q) {
+                            const uint32_t code = (word >> (q * b)) & mask;
+                            const float scaled = (float)code * S;      // Eq. 5: product rounded, then sum rounded
+                            const float value = scaled + Z;
+                            acc[v][q] = acc[v][q] + value;
+                        }
                     }
                 }
             }
@@ -804,9 +819,18 @@ extern "C" int adaqp_unpack_dequant_add(const uint8_t *packed_dev, int64_t packe
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid((unsigned)blocks);
     const int vw = vector_width(grad_dev, ld, dim, true);
-    if (vw == 4) hipLaunchKernelGGL(unpack_dequant_add_kernel<4>, grid, dim3(kBlock), 0, st, a);
-    else if (vw == 2) hipLaunchKernelGGL(unpack_dequant_add_kernel<2>, grid, dim3(kBlock), 0, st, a);
-    else hipLaunchKernelGGL(unpack_dequant_add_kernel<1>, grid, dim3(kBlock), 0, st, a);
+    const int nv = (dim + kWave * vw - 1) / (kWave * vw);          // rows wider than 4 vectors per lane: chunks of 4
+#define ADAQP_ADD(VW_)                                                                                             \
+    do {                                                                                                           \
+        if (nv == 1) hipLaunchKernelGGL((unpack_dequant_add_kernel<VW_, 1>), grid, dim3(kBlock), 0, st, a);        \
+        else if (nv == 2) hipLaunchKernelGGL((unpack_dequant_add_kernel<VW_, 2>), grid, dim3(kBlock), 0, st, a);   \
+        else if (nv == 3) hipLaunchKernelGGL((unpack_dequant_add_kernel<VW_, 3>), grid, dim3(kBlock), 0, st, a);   \
+        else hipLaunchKernelGGL((unpack_dequant_add_kernel<VW_, 4>), grid, dim3(kBlock), 0, st, a);                \
+    } while (0)
+    if (vw == 4) ADAQP_ADD(4);
+    else if (vw == 2) ADAQP_ADD(2);
+    else ADAQP_ADD(1);
+#undef ADAQP_ADD
     ADAQP_HIP_TRY(hipGetLastError());
     return ADAQP_OK;
 }
