@@ -46,6 +46,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_quantize_pack.restype = ctypes.c_int
         L.oracle_unpack_dequant.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, i64, vp]
         L.oracle_unpack_dequant.restype = ctypes.c_int
+        L.oracle_trace_beta.argtypes = [vp, i64, i32, vp, vp, i64, vp]
+        L.oracle_trace_beta.restype = ctypes.c_int
         L.oracle_unpack_dequant_add.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, i64]
         L.oracle_unpack_dequant_add.restype = ctypes.c_int
         L.oracle_spmm_csr.argtypes = [vp, vp, vp, i64, i64, vp, i64, i32, vp, i64, vp, vp]
@@ -129,6 +131,18 @@ def unpack_dequant(packed: np.ndarray, params: np.ndarray, bits: np.ndarray, row
     if rc != 0:
         raise ValueError(f"oracle_unpack_dequant failed: {rc}")
     return codes
+
+
+def trace_beta(feat: np.ndarray, dim: int, send_idx: np.ndarray, alpha_sq: np.ndarray) -> np.ndarray:
+    """beta[s] = alpha_sq[s] * dim * (max - min)^2 / 6 of row send_idx[s] (Sec. 4.2)."""
+    assert feat.dtype == np.float32 and feat.ndim == 2 and feat.flags.c_contiguous
+    send_idx = _chk(send_idx, np.int32)
+    alpha_sq = _chk(alpha_sq, np.float32)
+    beta = np.zeros(send_idx.shape[0], dtype=np.float32)
+    rc = lib().oracle_trace_beta(_p(feat), feat.shape[1], dim, _p(send_idx), _p(alpha_sq), send_idx.shape[0], _p(beta))
+    if rc != 0:
+        raise ValueError(f"oracle_trace_beta failed: {rc}")
+    return beta
 
 
 def unpack_dequant_add(packed: np.ndarray, params: np.ndarray, bits: np.ndarray, row_offset: np.ndarray,

@@ -169,6 +169,30 @@ int oracle_quantize_pack(const float *feat, int64_t ld, int32_t dim,
 }
 
 /* ------------------------------------------------------------------------------------------------------ */
+/* Trace for the bit-width assigner (Sec. 4.2): beta_k = (sum_v alpha_{k,v}^2) * D * (max(h_k) - min(h_k))^2 / 6, */
+/* the numerator of message k's term in the variance objective (Eq. 8).  alpha_sq[s] is the per-message sum   */
+/* of squared coefficients (an input: it lives on the target device).  fp32, in the order written.           */
+/* ------------------------------------------------------------------------------------------------------ */
+int oracle_trace_beta(const float *feat, int64_t ld, int32_t dim, const int32_t *send_idx,
+                      const float *alpha_sq, int64_t n_send, float *beta)
+{
+    if (n_send < 0 || dim <= 0 || ld < dim) return ORACLE_EINVAL;
+    for (int64_t s = 0; s < n_send; ++s) {
+        const float *h = feat + (int64_t)send_idx[s] * ld;
+        float mn = h[0], mx = h[0];
+        for (int32_t j = 1; j < dim; ++j) {
+            if (h[j] < mn) mn = h[j];
+            if (h[j] > mx) mx = h[j];
+        }
+        const float range = (mx + 0.0f) - (mn + 0.0f);
+        const float wd = alpha_sq[s] * (float)dim;
+        const float r2 = range * range;
+        beta[s] = (wd * r2) / 6.0f;
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------------------------ */
 /* Unpack + de-quantise into the halo rows (Eq. 5).  codes_out optional as above.                           */
 /* ------------------------------------------------------------------------------------------------------ */
 int oracle_unpack_dequant(const uint8_t *packed, const float *params,

@@ -311,3 +311,37 @@ def test_dequant_add_equals_dequant_on_zero_rows_and_is_sequential(oracle):
             want2 = want2 + plain[t]
         assert np.array_equal(grad2[0], want2)
         assert np.allclose(grad2[0], grad[0], rtol=1e-5, atol=1e-6)
+
+
+# ------------------------------------------------------------------------------------------------------
+# trace for the bit-width assigner: beta_k of Sec. 4.2
+# ------------------------------------------------------------------------------------------------------
+
+def test_beta_closed_forms(oracle):
+    idx = np.arange(3, dtype=np.int32)
+    rows = np.stack([np.arange(16), np.full(16, 2.5), np.arange(16) * 4 - 7]).astype(np.float32)
+    w = np.array([1.5, 2.0, 0.25], dtype=np.float32)
+    beta = oracle.trace_beta(rows, 16, idx, w)
+    assert beta[0] == np.float32(1.5 * 16 * 15 * 15 / 6)          # range 15
+    assert beta[1] == 0.0                                          # constant row
+    assert beta[2] == np.float32(0.25 * 16 * 60 * 60 / 6)         # range 60
+    # (max - min)^2 scaling: a power-of-two factor on the row scales beta by its square, exactly
+    assert np.array_equal(oracle.trace_beta(rows * np.float32(4), 16, idx, w), beta * np.float32(16))
+    # only the first dim columns count, and the row is found through send_idx
+    wide = np.concatenate([rows, np.full((3, 2), 1e6, np.float32)], axis=1)
+    assert np.array_equal(oracle.trace_beta(np.ascontiguousarray(wide), 16, idx[::-1].copy(), w[::-1].copy()), beta[::-1])
+
+
+@pytest.mark.parametrize("b", WIDTHS)
+def test_beta_is_the_variance_numerator_of_eq8(oracle, b):
+    """Eq. 8 charges message k with beta_k / (2^b - 1)^2.  With alpha^2 summing to 1 that is D S^2 / 6, the
+    variance Theorem 1 gives for the de-quantised message; compare with the variance measured over seeds."""
+    D, L = 4096, (1 << b) - 1
+    rng = np.random.default_rng(70 + b)
+    row = rng.uniform(0, L, size=D).astype(np.float32)
+    row[0], row[1] = 0.0, float(L)
+    beta = oracle.trace_beta(row[None, :], D, np.zeros(1, np.int32), np.ones(1, np.float32))
+    _, var, params = _moments_over_seeds(oracle, row[None, :], b, 2000)
+    assert abs(var.sum() / (float(beta[0]) / (L * L)) - 1) < 0.04
+    S = float(params[0, 1])
+    assert abs(float(beta[0]) / (L * L) - D * S * S / 6) <= 1e-6 * D * S * S
