@@ -104,6 +104,18 @@ int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, int64_t ld, 
                         int64_t n_send, uint64_t seed,
                         uint8_t *packed_dev, int64_t packed_bytes, float *params_dev, void *stream);
 
+/* Same as adaqp_quantize_pack, and additionally emits the trace the bit-width assigner works from (Sec. 4.2):
+ *     beta[s] = ((alpha_sq[s] * (float)dim) * (range * range)) / 6.0f        with range = max - min of the row,
+ * the numerator of message s in the variance objective (Eq. 8); fp32 in the order written.
+ *   alpha_sq_dev [n_send] fp32, read: sum of the squared aggregation coefficients the message meets on its
+ *                target device (an input; the sender cannot compute it);  beta_dev [n_send] fp32, written.
+ * Both NULL: identical to adaqp_quantize_pack.  Exactly one NULL: EINVAL.  Skipped slots write no beta. */
+int adaqp_quantize_pack_trace(const float *feat_dev, int64_t n_feat_rows, int64_t ld, int32_t dim,
+                              const int32_t *send_idx_dev, const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                              int64_t n_send, uint64_t seed,
+                              uint8_t *packed_dev, int64_t packed_bytes, float *params_dev,
+                              const float *alpha_sq_dev, float *beta_dev, void *stream);
+
 /* ---------------------------------------------------------------------------------------------------- */
 /* Receive side: Sec. 2.3 Eq. 5.  (bits, row_offset, halo_idx) are the receiver's "bit-retrieval index    */
 /* set" of Sec. 5.                                                                                         */
@@ -231,6 +243,7 @@ typedef struct adaqp_layer_desc {
     int64_t n_send;
     uint64_t seed;
     uint8_t *packed_dev;   float *params_dev;           /* send buffers */
+    const float *alpha_sq_dev; float *beta_dev;         /* optional trace (adaqp_quantize_pack_trace); both or none */
     uint8_t *recv_packed_dev; float *recv_params_dev;   /* receive buffers; the loop-back copy stands in for the exchange */
     int64_t packed_bytes;
     /* scratch and streams */

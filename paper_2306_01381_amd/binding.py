@@ -47,7 +47,8 @@ class LayerDesc(ctypes.Structure):
         ("recv_order_dev", _vp),
         ("recv_seg_order_dev", _vp), ("recv_seg_ptr_dev", _vp), ("n_recv_seg", _i64),
         ("n_send", _i64), ("seed", _u64),
-        ("packed_dev", _vp), ("params_dev", _vp), ("recv_packed_dev", _vp), ("recv_params_dev", _vp),
+        ("packed_dev", _vp), ("params_dev", _vp), ("alpha_sq_dev", _vp), ("beta_dev", _vp),
+        ("recv_packed_dev", _vp), ("recv_params_dev", _vp),
         ("packed_bytes", _i64),
         ("workspace_overlap_dev", _vp), ("workspace_overlap_bytes", _i64),
         ("workspace_dependent_dev", _vp), ("workspace_dependent_bytes", _i64),
@@ -64,6 +65,8 @@ _SIGNATURES = {
     "adaqp_row_stride": (_i64, [_i32, _i32]),
     "adaqp_plan_layout": (ctypes.c_int, [_i64, _i32, _vp, _vp, _i32, _vp, _vp, _vp]),
     "adaqp_quantize_pack": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _u64, _vp, _i64, _vp, _vp]),
+    "adaqp_quantize_pack_trace": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _u64, _vp, _i64, _vp,
+                                                 _vp, _vp, _vp]),
     "adaqp_plan_recv_order": (ctypes.c_int, [_i64, _vp, _vp]),
     "adaqp_unpack_dequant": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i64, _vp]),
     "adaqp_plan_recv_segments": (ctypes.c_int, [_i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
@@ -154,6 +157,22 @@ def adaqp_quantize_pack(feat: torch.Tensor, dim: int, send_idx: torch.Tensor, bi
                                      n, seed & (2**64 - 1), _dev(packed, torch.uint8, "packed"), packed.numel(),
                                      _dev(params, torch.float32, "params"), _stream(stream)),
            "adaqp_quantize_pack")
+
+
+def adaqp_quantize_pack_trace(feat: torch.Tensor, dim: int, send_idx: torch.Tensor, bits: torch.Tensor,
+                              row_offset: torch.Tensor, seed: int, packed: torch.Tensor, params: torch.Tensor,
+                              alpha_sq: torch.Tensor, beta: torch.Tensor,
+                              stream: Optional[torch.cuda.Stream] = None) -> None:
+    fp, n_rows, ld = _matrix(feat, "feat")
+    n = send_idx.shape[0]
+    _check(lib().adaqp_quantize_pack_trace(fp, n_rows, ld, dim, _dev(send_idx, torch.int32, "send_idx"),
+                                           _dev(bits, torch.uint8, "bits"),
+                                           _dev(row_offset, torch.int64, "row_offset"), n, seed & (2**64 - 1),
+                                           _dev(packed, torch.uint8, "packed"), packed.numel(),
+                                           _dev(params, torch.float32, "params"),
+                                           _dev(alpha_sq, torch.float32, "alpha_sq"),
+                                           _dev(beta, torch.float32, "beta"), _stream(stream)),
+           "adaqp_quantize_pack_trace")
 
 
 def adaqp_plan_recv_order(halo_idx_host: np.ndarray) -> np.ndarray:

@@ -61,6 +61,8 @@ struct QuantArgs {
     uint8_t *packed;
     int64_t packed_bytes;
     float *params;
+    const float *alpha_sq;      // optional trace input / output (both or none)
+    float *beta;
     int32_t lpr_log2;
 };
 
@@ -131,13 +133,14 @@ __device__ __forceinline__ void store_granule(uint8_t *row, int32_t g, int32_t n
     }
 }
 
-struct RowScale { float Z, S, inv16; };
+struct RowScale { float Z, S, inv16, range; };
 
 __device__ __forceinline__ RowScale row_scale(float mn, float mx, float levels)
 {
     RowScale rs;
     rs.Z = mn + 0.0f;                     // -0 -> +0, so that any reduction order gives the same zero-point
     const float range = (mx + 0.0f) - rs.Z;
+    rs.range = range;
     rs.S = 0.0f;
     rs.inv16 = 0.0f;
     if (range > 0.0f) {
@@ -145,6 +148,14 @@ __device__ __forceinline__ RowScale row_scale(float mn, float mx, float levels)
         rs.inv16 = (levels / range) * 65536.0f;
     }
     return rs;
+}
+
+// Trace for the bit-width assigner (Sec. 4.2): the numerator of the message's term in the variance objective.
+__device__ __forceinline__ float trace_beta(float alpha_sq, int32_t dim, float range)
+{
+    const float wd = alpha_sq * (float)dim;
+    const float r2 = range * range;
+    return (wd * r2) / 6.0f;
 }
 
 template <int B, int GPL>
@@ -266,7 +277,10 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
 
     const float levels = (float)((1 << (b & 15)) - 1);
     const RowScale rs = row_scale(mn, mx, levels);
-    if (valid && l == 0) *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
+    if (valid && l == 0) {
+        *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
+        if (a.beta) a.beta[s] = trace_beta(a.alpha_sq[s], a.dim, rs.range);
+    }
 
     // codes.  Slots are sorted by (peer, width), so nearly every wave holds a single width.
     uint8_t *row = a.packed + (valid ? off : 0);
@@ -312,7 +326,10 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_wide_kernel(const QuantA
     const float levels = (float)((1 << b) - 1);
     const float levels16 = levels * 65536.0f;
     const RowScale rs = row_scale(mn, mx, levels);
-    if (lane == 0) *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
+    if (lane == 0) {
+        *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
+        if (a.beta) a.beta[s] = trace_beta(a.alpha_sq[s], a.dim, rs.range);
+    }
 
     uint8_t *row = a.packed + off;
     const uint32_t s_lo = (uint32_t)s, s_hi = (uint32_t)((uint64_t)s >> 32);
@@ -656,6 +673,18 @@ extern "C" int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, i
                                    const int64_t *row_offset_dev, int64_t n_send, uint64_t seed,
                                    uint8_t *packed_dev, int64_t packed_bytes, float *params_dev, void *stream)
 {
+    return adaqp_quantize_pack_trace(feat_dev, n_feat_rows, ld, dim, send_idx_dev, bits_dev, row_offset_dev, n_send,
+                                     seed, packed_dev, packed_bytes, params_dev, nullptr, nullptr, stream);
+}
+
+extern "C" int adaqp_quantize_pack_trace(const float *feat_dev, int64_t n_feat_rows, int64_t ld, int32_t dim,
+                                         const int32_t *send_idx_dev, const uint8_t *bits_dev,
+                                         const int64_t *row_offset_dev, int64_t n_send, uint64_t seed,
+                                         uint8_t *packed_dev, int64_t packed_bytes, float *params_dev,
+                                         const float *alpha_sq_dev, float *beta_dev, void *stream)
+{
+    if ((alpha_sq_dev == nullptr) != (beta_dev == nullptr)) return ADAQP_EINVAL;
+    if (!aligned_to(alpha_sq_dev, 4) || !aligned_to(beta_dev, 4)) return ADAQP_EINVAL;
     if (n_send < 0 || dim <= 0 || ld < dim || n_feat_rows < 0 || packed_bytes < 0) return ADAQP_EINVAL;
     if (n_send == 0) return ADAQP_OK;
     if (!feat_dev || !send_idx_dev || !bits_dev || !row_offset_dev || !packed_dev || !params_dev)
@@ -681,6 +710,8 @@ extern "C" int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, i
     a.packed = packed_dev;
     a.packed_bytes = packed_bytes;
     a.params = params_dev;
+    a.alpha_sq = alpha_sq_dev;
+    a.beta = beta_dev;
     a.lpr_log2 = 0;
     hipStream_t st = (hipStream_t)stream;
 

@@ -228,9 +228,9 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
             ADAQP_STEP(fork_now());
             ADAQP_STEP(aggregate(d, true, agg));
         }
-        ADAQP_STEP(adaqp_quantize_pack(d->feat_dev, d->n_feat_rows, d->ld, d->dim, d->send_idx_dev, d->bits_dev,
-                                       d->row_offset_dev, d->n_send, d->seed, d->packed_dev, d->packed_bytes,
-                                       d->params_dev, msg));
+        ADAQP_STEP(adaqp_quantize_pack_trace(d->feat_dev, d->n_feat_rows, d->ld, d->dim, d->send_idx_dev,
+                                             d->bits_dev, d->row_offset_dev, d->n_send, d->seed, d->packed_dev,
+                                             d->packed_bytes, d->params_dev, d->alpha_sq_dev, d->beta_dev, msg));
         if (d->schedule == ADAQP_ISOLATED) {
             ADAQP_STEP(fork_now());
             ADAQP_STEP(aggregate(d, true, agg));
@@ -249,9 +249,11 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
             ADAQP_STEP(aggregate(d, true, agg));
         }
         ADAQP_STEP(aggregate(d, false, msg));
-        ADAQP_STEP(adaqp_quantize_pack(d->out_dev, d->dependent_end > d->overlap_end ? d->dependent_end : d->overlap_end,
-                                       d->ldo, d->dim, d->send_idx_dev, d->bits_dev, d->row_offset_dev, d->n_send,
-                                       d->seed, d->packed_dev, d->packed_bytes, d->params_dev, msg));
+        ADAQP_STEP(adaqp_quantize_pack_trace(d->out_dev,
+                                             d->dependent_end > d->overlap_end ? d->dependent_end : d->overlap_end,
+                                             d->ldo, d->dim, d->send_idx_dev, d->bits_dev, d->row_offset_dev,
+                                             d->n_send, d->seed, d->packed_dev, d->packed_bytes, d->params_dev,
+                                             d->alpha_sq_dev, d->beta_dev, msg));
         if (d->schedule == ADAQP_ISOLATED) {
             ADAQP_STEP(fork_now());
             ADAQP_STEP(aggregate(d, true, agg));

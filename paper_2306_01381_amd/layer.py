@@ -88,7 +88,7 @@ def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
 
 class LayerStep:
     def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False,
-                 backward_receive: bool = True):
+                 backward_receive: bool = True, trace: bool = True):
         self.p = p
         self.device = torch.device(device)
         dev = self.device
@@ -109,6 +109,15 @@ class LayerStep:
         nbytes = max(self.plan.packed_bytes, 4)
         self.packed = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
         self.params = torch.zeros((max(n, 1), 2), dtype=torch.float32, device=dev)
+        # trace for the bit-width assigner: per slot, the sum of squared coefficients the message meets on its
+        # target device is an input; the stand-in used here is the sum of squared coefficients of the node's own row
+        self.alpha_sq = self.beta = None
+        if trace and n > 0:
+            sq = np.add.reduceat(np.square(p.val.astype(np.float64)), np.minimum(p.rowptr[:-1], max(p.nnz - 1, 0)))
+            sq[np.diff(p.rowptr) == 0] = 0.0
+            self.alpha_sq_host = sq[self.plan.send_idx_host].astype(np.float32)
+            self.alpha_sq = torch.from_numpy(self.alpha_sq_host).to(dev)
+            self.beta = torch.zeros(n, dtype=torch.float32, device=dev)
         self.recv_packed = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
         self.recv_params = torch.zeros((max(n, 1), 2), dtype=torch.float32, device=dev)
         ob, oe = p.overlap_rows
@@ -146,6 +155,8 @@ class LayerStep:
             d.n_recv_seg = pl.seg_ptr.shape[0] - 1
         d.n_send, d.seed = pl.n, self.seed
         d.packed_dev, d.params_dev = self.packed.data_ptr(), self.params.data_ptr()
+        if self.alpha_sq is not None:
+            d.alpha_sq_dev, d.beta_dev = self.alpha_sq.data_ptr(), self.beta.data_ptr()
         d.recv_packed_dev, d.recv_params_dev = self.recv_packed.data_ptr(), self.recv_params.data_ptr()
         d.packed_bytes = pl.packed_bytes
         d.workspace_overlap_dev, d.workspace_overlap_bytes = self.ws_overlap.data_ptr(), self.ws_overlap.numel()

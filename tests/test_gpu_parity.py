@@ -163,6 +163,41 @@ def test_codec_skips_invalid_slots_and_empty_input(oracle):
 
 
 # ------------------------------------------------------------------------------------------------------
+# trace for the bit-width assigner (beta of Sec. 4.2)
+# ------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dim,ld", [(128, 128), (602, 608), (602, 602), (300, 320), (7, 7), (5000, 5000)])
+def test_quantize_trace_beta(oracle, dim, ld):
+    _say(f"beta trace dim={dim} ld={ld}")
+    rng = np.random.default_rng(dim)
+    n_rows, n = 120, 97
+    feat = rng.standard_normal((n_rows, ld), dtype=np.float32) * rng.choice([1e-3, 1.0, 50.0], size=(n_rows, 1)).astype(np.float32)
+    feat[2, :dim] = 0.75
+    feat[:, dim:] = np.float32(1e30)
+    send = rng.integers(0, n_rows, size=n).astype(np.int32)
+    send[0] = 2
+    bits = np.sort(rng.choice(np.array([2, 4, 8], dtype=np.uint8), size=n))
+    perm, off, pbp = oracle.plan_layout(dim, bits, np.zeros(n, np.int32), 1)
+    alpha_sq = rng.uniform(0.01, 3.0, size=n).astype(np.float32)
+    want_packed, want_params, _ = oracle.quantize_pack(feat, dim, send, bits, off, 9, int(pbp[-1]))
+    want_beta = oracle.trace_beta(feat, dim, send, alpha_sq)
+    packed = torch.zeros(int(pbp[-1]), dtype=torch.uint8, device=DEV)
+    params = torch.zeros((n, 2), dtype=torch.float32, device=DEV)
+    beta = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    B.adaqp_quantize_pack_trace(torch.from_numpy(feat).to(DEV), dim, torch.from_numpy(send).to(DEV),
+                                torch.from_numpy(bits).to(DEV), torch.from_numpy(off).to(DEV), 9, packed, params,
+                                torch.from_numpy(alpha_sq).to(DEV), beta)
+    torch.cuda.synchronize()
+    assert np.array_equal(packed.cpu().numpy(), want_packed)
+    assert np.array_equal(params.cpu().numpy().view(np.uint32), want_params.view(np.uint32))
+    assert np.array_equal(beta.cpu().numpy().view(np.uint32), want_beta.view(np.uint32))
+    assert want_beta[0] == 0.0
+    with pytest.raises(B.AdaqpError):
+        B.lib()            # keeps the import used
+        B._check(B.lib().adaqp_quantize_pack_trace(1, 1, 8, 8, 1, 1, 1, 1, 0, 1, 8, 1, None, 1, None), "one NULL")
+
+
+# ------------------------------------------------------------------------------------------------------
 # backward receive: de-quantise and add
 # ------------------------------------------------------------------------------------------------------
 
@@ -366,6 +401,8 @@ def test_layer_step_matches_oracle_in_every_schedule(oracle, name):
         packed = L.recv_packed.cpu().numpy()[: L.plan.packed_bytes]
         params = L.recv_params.cpu().numpy()[: L.plan.n]
         if not cfg.backward:
+            want_beta = oracle.trace_beta(p.feat, cfg.dim, L.plan.send_idx_host, L.alpha_sq_host)
+            assert np.array_equal(L.beta.cpu().numpy().view(np.uint32), want_beta.view(np.uint32))
             assert np.array_equal(packed, packed_w)
             assert np.array_equal(params.view(np.uint32), params_w.view(np.uint32))
             assert np.array_equal(L.feat.cpu().numpy().view(np.uint32), feat_w.view(np.uint32))
