@@ -166,6 +166,17 @@ def main():
         return (time.perf_counter() - t) * 1e3 / steps
 
     ms_per_step = timed_steps(sched[args.schedule], args.steps, args.warmup)
+    # variant (not the headline): the dependent aggregation de-quantises received rows in registers, straight
+    # from the receive buffer, instead of reading rows that a separate kernel wrote into the feature matrix
+    fused = None
+    if not cfg.backward:
+        L.set_fused_receive(True)
+        ms_fused = timed_steps(sched[args.schedule], args.steps, args.warmup)
+        L.set_fused_receive(False)
+        timed_steps(sched[args.schedule], 1, 0)         # leaves feat's halo rows as the plain step writes them
+        fused = {"ms_per_step": ms_fused, "value": p.nnz / ms_fused * 1e3, "unit": "edges/s",
+                 "note": "adaqp_spmm_csr_packed for the marginal rows, no adaqp_unpack_dequant launch; "
+                         "output bit-identical to the plain step"}
     other = {}
     for name, s in sched.items():
         if name == args.schedule:
@@ -282,6 +293,7 @@ def main():
                    "packed_bytes": pl.packed_bytes, "direction": p.meta["direction"],
                    "schedule": args.schedule, "seed": cfg.seed},
         "ms_per_step_by_schedule": other,
+        "fused_receive_variant": fused,
         "kernels": kernels,
         "roofline": roofline,
         "setup_s": {"generate": t_gen},
@@ -291,7 +303,8 @@ def main():
         # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/README.md)
         entry = json.load(open(traffic_file)).get(cfg.name, {}).get("spmm_merge_kernel")
         if entry:
-            roofline["traffic"] = entry
+            roofline["traffic"] = entry["fetch"] + entry["write"]       # HBM bytes per launch, read + written
+            roofline["traffic_detail"] = entry
     if args.calibrate:
         a_ = torch.zeros(1 << 26, dtype=torch.float32, device=dev)
         b_ = torch.empty_like(a_)

@@ -193,6 +193,26 @@ int adaqp_spmm_csr(const int64_t *rowptr_dev, const int32_t *col_dev, const floa
                    float *out_dev, int64_t ldo,
                    void *workspace_dev, int64_t workspace_bytes, void *stream);
 
+/* Host only: inverse of halo_idx.  slot_of_row_out[n_rows] = t for the row halo_idx_host[t], -1 for every
+ * other row.  Errors: EINVAL (index out of range, a row listed twice), ESIZE (n > 2^31 - 1). */
+int adaqp_plan_slot_of_row(int64_t n_rows, int64_t n, const int32_t *halo_idx_host, int32_t *slot_of_row_out);
+
+/* adaqp_spmm_csr with some rows of H still packed: an entry whose column c has slot_of_row[c] = t >= 0 takes
+ * the neighbour row from the receive buffer (packed + row_offset[t], bits[t], params[t]) and de-quantises it
+ * in registers, (float)code * S + Z with the two roundings of Eq. 5, instead of reading H[c].  The result is
+ * bit-identical to adaqp_unpack_dequant into H followed by adaqp_spmm_csr; the rows of H are neither written
+ * nor read.  A slot that is out of range falls back to H[c].  slot_of_row_dev NULL: plain adaqp_spmm_csr.
+ *   slot_of_row_dev [n_cols] int32;  per-slot arrays [n_slots] as for adaqp_unpack_dequant.
+ * Errors: as adaqp_spmm_csr; EINVAL if slot_of_row_dev is given without the per-slot arrays. */
+int adaqp_spmm_csr_packed(const int64_t *rowptr_dev, const int32_t *col_dev, const float *val_dev, int64_t nnz,
+                          int64_t row_begin, int64_t row_end, int64_t nnz_range,
+                          const float *H_dev, int64_t n_cols, int64_t ldh, int32_t dim,
+                          float *out_dev, int64_t ldo,
+                          const int32_t *slot_of_row_dev, const uint8_t *packed_dev, int64_t packed_bytes,
+                          const float *params_dev, const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                          int64_t n_slots,
+                          void *workspace_dev, int64_t workspace_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------------- */
 /* One layer's aggregation step with the message path overlapped (Sec. 3.1, Sec. 3.4 Fig. 7).             */
 /* ---------------------------------------------------------------------------------------------------- */
@@ -237,6 +257,9 @@ typedef struct adaqp_layer_desc {
     const int64_t *row_offset_dev;
     const int32_t *halo_idx_dev;    /* forward only: destination rows of the received slots */
     const int32_t *recv_order_dev;  /* forward only, optional: adaqp_plan_recv_order of halo_idx */
+    const int32_t *slot_of_row_dev; /* forward only, optional: adaqp_plan_slot_of_row of halo_idx.  If given, the
+                                       received rows are NOT de-quantised into feat; the dependent aggregation
+                                       reads them from the receive buffer (adaqp_spmm_csr_packed) */
     const int32_t *recv_seg_order_dev;  /* backward only, optional: adaqp_plan_recv_segments of halo_idx */
     const int64_t *recv_seg_ptr_dev;
     int64_t n_recv_seg;

@@ -45,6 +45,7 @@ class LayerDesc(ctypes.Structure):
         ("out_dev", _vp), ("ldo", _i64),
         ("send_idx_dev", _vp), ("bits_dev", _vp), ("row_offset_dev", _vp), ("halo_idx_dev", _vp),
         ("recv_order_dev", _vp),
+        ("slot_of_row_dev", _vp),
         ("recv_seg_order_dev", _vp), ("recv_seg_ptr_dev", _vp), ("n_recv_seg", _i64),
         ("n_send", _i64), ("seed", _u64),
         ("packed_dev", _vp), ("params_dev", _vp), ("alpha_sq_dev", _vp), ("beta_dev", _vp),
@@ -75,6 +76,9 @@ _SIGNATURES = {
     "adaqp_spmm_workspace_bytes": (ctypes.c_int, [_i64, _i64, _i32, ctypes.POINTER(_i64)]),
     "adaqp_spmm_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
                                       _vp, _i64, _vp, _i64, _vp]),
+    "adaqp_plan_slot_of_row": (ctypes.c_int, [_i64, _i64, _vp, _vp]),
+    "adaqp_spmm_csr_packed": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
+                                             _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "adaqp_layer_step": (ctypes.c_int, [ctypes.POINTER(LayerDesc)]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -241,6 +245,34 @@ def adaqp_spmm_csr(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, r
                                 hp, n_cols, ldh, dim, op, ldo, _dev(workspace, torch.uint8, "workspace"),
                                 workspace.numel(), _stream(stream)),
            "adaqp_spmm_csr")
+
+
+def adaqp_plan_slot_of_row(n_rows: int, halo_idx_host: np.ndarray) -> np.ndarray:
+    """Host-only.  Returns int32[n_rows]: the slot received into each row, -1 elsewhere."""
+    halo = np.ascontiguousarray(halo_idx_host, dtype=np.int32)
+    out = np.zeros(n_rows, dtype=np.int32)
+    _check(lib().adaqp_plan_slot_of_row(n_rows, halo.shape[0], halo.ctypes.data, out.ctypes.data),
+           "adaqp_plan_slot_of_row")
+    return out
+
+
+def adaqp_spmm_csr_packed(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, row_begin: int, row_end: int,
+                          H: torch.Tensor, dim: int, out: torch.Tensor, slot_of_row: torch.Tensor,
+                          packed: torch.Tensor, params: torch.Tensor, bits: torch.Tensor, row_offset: torch.Tensor,
+                          workspace: torch.Tensor, nnz_range: int = -1,
+                          stream: Optional[torch.cuda.Stream] = None) -> None:
+    hp, n_cols, ldh = _matrix(H, "H")
+    op, _, ldo = _matrix(out, "out")
+    _check(lib().adaqp_spmm_csr_packed(_dev(rowptr, torch.int64, "rowptr"), _dev(col, torch.int32, "col"),
+                                       _dev(val, torch.float32, "val"), col.numel(), row_begin, row_end, nnz_range,
+                                       hp, n_cols, ldh, dim, op, ldo,
+                                       _dev(slot_of_row, torch.int32, "slot_of_row"),
+                                       _dev(packed, torch.uint8, "packed"), packed.numel(),
+                                       _dev(params, torch.float32, "params"), _dev(bits, torch.uint8, "bits"),
+                                       _dev(row_offset, torch.int64, "row_offset"), bits.shape[0],
+                                       _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                       _stream(stream)),
+           "adaqp_spmm_csr_packed")
 
 
 def adaqp_layer_step(desc: LayerDesc) -> None:

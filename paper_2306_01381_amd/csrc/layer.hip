@@ -102,6 +102,22 @@ extern "C" int adaqp_plan_recv_order(int64_t n, const int32_t *halo_idx_host, in
     return ADAQP_OK;
 }
 
+extern "C" int adaqp_plan_slot_of_row(int64_t n_rows, int64_t n, const int32_t *halo_idx_host,
+                                      int32_t *slot_of_row_out)
+{
+    if (n_rows < 0 || n < 0) return ADAQP_EINVAL;
+    if (n_rows > 0 && !slot_of_row_out) return ADAQP_EINVAL;
+    if (n > 0 && !halo_idx_host) return ADAQP_EINVAL;
+    if (n > INT32_MAX) return ADAQP_ESIZE;
+    for (int64_t r = 0; r < n_rows; ++r) slot_of_row_out[r] = -1;
+    for (int64_t t = 0; t < n; ++t) {
+        const int32_t r = halo_idx_host[t];
+        if (r < 0 || r >= n_rows || slot_of_row_out[r] != -1) return ADAQP_EINVAL;
+        slot_of_row_out[r] = (int32_t)t;
+    }
+    return ADAQP_OK;
+}
+
 extern "C" int adaqp_plan_recv_segments(int64_t n, const int32_t *dst_idx_host, int32_t *order_out,
                                         int64_t *seg_ptr_out, int64_t *n_seg_out)
 {
@@ -156,6 +172,11 @@ int check_desc(const adaqp_layer_desc *d)
     return ADAQP_OK;
 }
 
+bool fused_receive(const adaqp_layer_desc *d)
+{
+    return d->direction == ADAQP_FORWARD && d->slot_of_row_dev && d->n_send > 0 && d->packed_bytes >= 4;
+}
+
 int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
 {
     const int64_t rb = overlap_part ? d->overlap_begin : d->dependent_begin;
@@ -163,6 +184,11 @@ int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
     const int64_t nz = overlap_part ? d->overlap_nnz : d->dependent_nnz;
     void *ws = overlap_part ? d->workspace_overlap_dev : d->workspace_dependent_dev;
     const int64_t wsb = overlap_part ? d->workspace_overlap_bytes : d->workspace_dependent_bytes;
+    if (!overlap_part && fused_receive(d))
+        return adaqp_spmm_csr_packed(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, nz, d->feat_dev,
+                                     d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, d->slot_of_row_dev,
+                                     d->recv_packed_dev, d->packed_bytes, d->recv_params_dev, d->bits_dev,
+                                     d->row_offset_dev, d->n_send, ws, wsb, st);
     return adaqp_spmm_csr(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, nz, d->feat_dev,
                           d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, ws, wsb, st);
 }
@@ -236,9 +262,10 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
             ADAQP_STEP(aggregate(d, true, agg));
         }
         ADAQP_STEP(loop_back(d, msg));
-        ADAQP_STEP(adaqp_unpack_dequant(d->recv_packed_dev, d->packed_bytes, d->recv_params_dev, d->bits_dev,
-                                        d->row_offset_dev, d->halo_idx_dev, d->recv_order_dev, d->n_send, d->dim, d->feat_dev,
-                                        d->n_feat_rows, d->ld, msg));
+        if (!fused_receive(d))
+            ADAQP_STEP(adaqp_unpack_dequant(d->recv_packed_dev, d->packed_bytes, d->recv_params_dev, d->bits_dev,
+                                            d->row_offset_dev, d->halo_idx_dev, d->recv_order_dev, d->n_send, d->dim,
+                                            d->feat_dev, d->n_feat_rows, d->ld, msg));
         if (d->schedule == ADAQP_SERIAL) ADAQP_STEP(aggregate(d, true, msg));
         ADAQP_STEP(aggregate(d, false, msg));
     } else {

@@ -36,6 +36,15 @@ struct SpmmArgs {
     float *carry;               // [n_items, carry_ld]
     int64_t carry_ld;
     int32_t n_items;
+    // optional: rows of H that are still packed (received halo rows, de-quantised on the fly)
+    const int32_t *slot_of_row; // [n_cols], -1 = read the row from H
+    const uint8_t *packed;
+    int64_t packed_bytes;
+    const float *params;
+    const uint8_t *bits;
+    const int64_t *row_offset;
+    int64_t n_slots;
+    int32_t col0, full_dim;     // first column of this launch's chunk and the row length of the packed layout
 };
 
 template <int VW> struct VecOf;
@@ -83,6 +92,13 @@ __device__ __forceinline__ int64_t uniform_i64(int64_t v)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
+__device__ __forceinline__ int64_t readlane_i64(int64_t v, int lane_id)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)v, lane_id);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)((uint64_t)v >> 32), lane_id);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 // Merge-path split point on diagonal d: the number of row ends that precede d path steps.  Row end i (its
 // entry count relative to the range is end_i) precedes entry j iff end_i <= j; on diagonal d this reads
 // end_i + i + 1 <= d, which is increasing in i, so the answer is the first i for which it fails.
@@ -113,7 +129,10 @@ __device__ int64_t split_rows(const SpmmArgs &a, int64_t d, int64_t base, int64_
 constexpr int32_t kNoRow = -1;
 constexpr int32_t kFar = 0x7FFFFFFF;
 
-template <int VW, int NV, int U>
+// PACKED: entries whose column has a slot in slot_of_row take the neighbour row from the packed receive buffer
+// and de-quantise it in registers, (float)code * S + Z as in Sec. 2.3 Eq. 5 (product rounded, then sum rounded),
+// so the result is bit-identical to de-quantising into H first - without writing and re-reading those rows.
+template <int VW, int NV, int U, bool PACKED>
 __global__ __launch_bounds__(kBlock) void spmm_merge_kernel(const SpmmArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -189,10 +208,27 @@ __global__ __launch_bounds__(kBlock) void spmm_merge_kernel(const SpmmArgs a)
         const int32_t nb = n_edges - j < kWave ? n_edges - j : kWave;
         int32_t my_col = 0;
         float my_val = 0.0f;
+        int32_t my_b = 0;                                   // PACKED: width of the entry's packed row, 0 = plain row
+        int64_t my_off = 0;
+        float my_z = 0.0f, my_s = 0.0f;
         if (lane < nb) {
             my_col = __builtin_nontemporal_load(colp + j + lane);     // streamed once: keep the caches for H
             my_val = __builtin_nontemporal_load(valp + j + lane);
             if (my_col < 0 || my_col >= a.n_cols) { my_col = 0; my_val = 0.0f; }   // out-of-range entry: skipped
+            if (PACKED) {
+                const int32_t slot = a.slot_of_row[my_col];
+                if (slot >= 0 && slot < a.n_slots) {
+                    my_b = a.bits[slot];
+                    my_off = a.row_offset[slot];
+                    const float2 zs = *reinterpret_cast<const float2 *>(a.params + 2 * (int64_t)slot);
+                    my_z = zs.x;
+                    my_s = zs.y;
+                    const int64_t stride = 4 * (((int64_t)a.full_dim * my_b + 31) >> 5);
+                    const bool ok = (my_b == 2 || my_b == 4 || my_b == 8) && my_off >= 0 && (my_off & 3) == 0 &&
+                                    my_off + stride <= a.packed_bytes;
+                    if (!ok) my_b = 0;                      // broken slot: fall back to the row in H
+                }
+            }
         }
         for (int32_t e = 0; e < nb; e += U) {
             float h[U][NV][VW];
@@ -200,14 +236,29 @@ __global__ __launch_bounds__(kBlock) void spmm_merge_kernel(const SpmmArgs a)
             for (int u = 0; u < U; ++u) {
                 const int32_t eu = e + u < nb ? e + u : nb - 1;                    // tail repeats the last entry
                 const int32_t c = __builtin_amdgcn_readlane(my_col, eu);
-                const float *hrow = a.H + (int64_t)c * a.ldh;
+                const int32_t pb = PACKED ? __builtin_amdgcn_readlane(my_b, eu) : 0;
+                if (PACKED && pb != 0) {                                           // wave-uniform
+                    // one 32-bit word holds the VW codes of a lane's vector (VW * b <= 32 and divides 32)
+                    const uint32_t *words = reinterpret_cast<const uint32_t *>(a.packed + readlane_i64(my_off, eu));
+                    const uint32_t last_word = (uint32_t)(((int64_t)a.full_dim * pb - 1) >> 5);
 #pragma unroll
-                for (int v = 0; v < NV; ++v) {
-                    if (v < NV - 1 || last_ok) {
-                        load_vec<VW>(hrow + (v * kWave + lane) * VW, h[u][v]);
-                    } else {
+                    for (int v = 0; v < NV; ++v) {
+                        const uint32_t bit = (uint32_t)(a.col0 + (v * kWave + lane) * VW) * (uint32_t)pb;
+                        const uint32_t idx = (bit >> 5) < last_word ? (bit >> 5) : last_word;
 #pragma unroll
                         for (int k = 0; k < VW; ++k) h[u][v][k] = 0.0f;
+                        h[u][v][0] = __builtin_bit_cast(float, words[idx]);
+                    }
+                } else {
+                    const float *hrow = a.H + (int64_t)c * a.ldh;
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) {
+                        if (v < NV - 1 || last_ok) {
+                            load_vec<VW>(hrow + (v * kWave + lane) * VW, h[u][v]);
+                        } else {
+#pragma unroll
+                            for (int k = 0; k < VW; ++k) h[u][v][k] = 0.0f;
+                        }
                     }
                 }
             }
@@ -217,10 +268,31 @@ __global__ __launch_bounds__(kBlock) void spmm_merge_kernel(const SpmmArgs a)
                     while (j >= cur_end && row < i1) flush_row();    // rows that end before this entry
                     const float alpha = __builtin_bit_cast(
                         float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_val), e + u));
+                    const int32_t pb = PACKED ? __builtin_amdgcn_readlane(my_b, e + u) : 0;
+                    if (PACKED && pb != 0) {
+                        const float Z = __builtin_bit_cast(
+                            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_z), e + u));
+                        const float S = __builtin_bit_cast(
+                            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_s), e + u));
+                        const uint32_t mask = (1u << pb) - 1u;
 #pragma unroll
-                    for (int v = 0; v < NV; ++v)
+                        for (int v = 0; v < NV; ++v) {
+                            const uint32_t bit = (uint32_t)(a.col0 + (v * kWave + lane) * VW) * (uint32_t)pb;
+                            const uint32_t word = __builtin_bit_cast(uint32_t, h[u][v][0]) >> (bit & 31u);
 #pragma unroll
-                        for (int k = 0; k < VW; ++k) acc[v][k] = fmaf(alpha, h[u][v][k], acc[v][k]);
+                            for (int k = 0; k < VW; ++k) {
+                                const uint32_t code = (word >> (k * pb)) & mask;
+                                const float scaled = (float)code * S;      // Eq. 5: product rounded, then sum rounded
+                                const float value = scaled + Z;
+                                acc[v][k] = fmaf(alpha, value, acc[v][k]);
+                            }
+                        }
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < NV; ++v)
+#pragma unroll
+                            for (int k = 0; k < VW; ++k) acc[v][k] = fmaf(alpha, h[u][v][k], acc[v][k]);
+                    }
                     ++j;
                     dirty = true;
                 }
@@ -327,7 +399,8 @@ template <int VW, int NV>
 hipError_t launch_merge(const SpmmArgs &a, dim3 grid, hipStream_t st)
 {
     constexpr int U = NV >= 4 ? 4 : (NV >= 2 ? 8 : 16);
-    hipLaunchKernelGGL((spmm_merge_kernel<VW, NV, U>), grid, dim3(kBlock), 0, st, a);
+    if (a.slot_of_row) hipLaunchKernelGGL((spmm_merge_kernel<VW, NV, U, true>), grid, dim3(kBlock), 0, st, a);
+    else hipLaunchKernelGGL((spmm_merge_kernel<VW, NV, U, false>), grid, dim3(kBlock), 0, st, a);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL((spmm_carry_kernel<VW, NV>), grid, dim3(kBlock), 0, st, a);
@@ -370,6 +443,27 @@ extern "C" int adaqp_spmm_csr(const int64_t *rowptr_dev, const int32_t *col_dev,
                               float *out_dev, int64_t ldo, void *workspace_dev, int64_t workspace_bytes,
                               void *stream)
 {
+    return adaqp_spmm_csr_packed(rowptr_dev, col_dev, val_dev, nnz, row_begin, row_end, nnz_range, H_dev, n_cols, ldh,
+                                 dim, out_dev, ldo, nullptr, nullptr, 0, nullptr, nullptr, nullptr, 0, workspace_dev,
+                                 workspace_bytes, stream);
+}
+
+extern "C" int adaqp_spmm_csr_packed(const int64_t *rowptr_dev, const int32_t *col_dev, const float *val_dev,
+                                     int64_t nnz, int64_t row_begin, int64_t row_end, int64_t nnz_range,
+                                     const float *H_dev, int64_t n_cols, int64_t ldh, int32_t dim,
+                                     float *out_dev, int64_t ldo,
+                                     const int32_t *slot_of_row_dev, const uint8_t *packed_dev, int64_t packed_bytes,
+                                     const float *params_dev, const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                                     int64_t n_slots,
+                                     void *workspace_dev, int64_t workspace_bytes, void *stream)
+{
+    if (slot_of_row_dev) {
+        if (!packed_dev || !params_dev || !bits_dev || !row_offset_dev || packed_bytes < 4 || n_slots <= 0)
+            return ADAQP_EINVAL;
+        if (!aligned_to(slot_of_row_dev, 4) || !aligned_to(packed_dev, 4) || !aligned_to(params_dev, 8) ||
+            !aligned_to(row_offset_dev, 8))
+            return ADAQP_EINVAL;
+    }
     if (row_begin < 0 || row_end < row_begin || nnz < 0 || dim <= 0 || ldh < dim || ldo < dim || n_cols < 0)
         return ADAQP_EINVAL;
     const int64_t n_rows = row_end - row_begin;
@@ -417,6 +511,15 @@ extern "C" int adaqp_spmm_csr(const int64_t *rowptr_dev, const int32_t *col_dev,
         a.carry = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace_dev) + g.carry_off);
         a.carry_ld = g.carry_ld;
         a.n_items = g.n_items;
+        a.slot_of_row = slot_of_row_dev;
+        a.col0 = c0;
+        a.full_dim = dim;
+        a.packed = packed_dev;
+        a.packed_bytes = packed_bytes;
+        a.params = params_dev;
+        a.bits = bits_dev;
+        a.row_offset = row_offset_dev;
+        a.n_slots = n_slots;
         const int nv = (a.wdim + kWave * vw - 1) / (kWave * vw);
         const dim3 grid((unsigned)((g.n_items + kWavesPerBlock - 1) / kWavesPerBlock));
         hipError_t err;

@@ -88,7 +88,7 @@ def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
 
 class LayerStep:
     def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False,
-                 backward_receive: bool = True, trace: bool = True):
+                 backward_receive: bool = True, trace: bool = True, fused_receive: bool = False):
         self.p = p
         self.device = torch.device(device)
         dev = self.device
@@ -98,6 +98,7 @@ class LayerStep:
         self.seed = seed
         self.use_recv_order = use_recv_order
         self.backward_receive = backward_receive
+        self.fused_receive = fused_receive and not self.backward
         self.rowptr = torch.from_numpy(p.rowptr).to(dev)
         self.col = torch.from_numpy(p.col).to(dev)
         self.val = torch.from_numpy(p.val).to(dev)
@@ -106,6 +107,9 @@ class LayerStep:
         self.plan = SendPlan(cfg.dim, p.send_idx, p.bits, p.peer_of_slot, cfg.n_peers, p.halo_idx, dev,
                              add_segments=self.backward)
         n = self.plan.n
+        # forward, fused receive: the dependent aggregation reads received rows straight from the receive buffer
+        self.slot_of_row = None
+        self.set_fused_receive(self.fused_receive)
         nbytes = max(self.plan.packed_bytes, 4)
         self.packed = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
         self.params = torch.zeros((max(n, 1), 2), dtype=torch.float32, device=dev)
@@ -133,6 +137,14 @@ class LayerStep:
         self.event_fork = HipEvent()
         self.event_join = HipEvent()
 
+    def set_fused_receive(self, on: bool) -> None:
+        """Forward only.  On: received rows are not de-quantised into feat; the dependent aggregation reads
+        them from the receive buffer."""
+        self.fused_receive = bool(on) and not self.backward and self.plan.halo_idx_host is not None
+        if self.fused_receive and self.slot_of_row is None:
+            self.slot_of_row = torch.from_numpy(
+                B.adaqp_plan_slot_of_row(self.p.feat.shape[0], self.plan.halo_idx_host)).to(self.device)
+
     def desc(self, schedule: int) -> B.LayerDesc:
         p, pl = self.p, self.plan
         d = B.LayerDesc()
@@ -150,6 +162,7 @@ class LayerStep:
         d.halo_idx_dev = None if pl.halo_idx is None else pl.halo_idx.data_ptr()
         d.recv_order_dev = pl.recv_order.data_ptr() if (self.use_recv_order and pl.recv_order is not None
                                                         and not self.backward) else None
+        d.slot_of_row_dev = self.slot_of_row.data_ptr() if self.fused_receive else None
         if self.backward and self.backward_receive and pl.seg_order is not None:
             d.recv_seg_order_dev, d.recv_seg_ptr_dev = pl.seg_order.data_ptr(), pl.seg_ptr.data_ptr()
             d.n_recv_seg = pl.seg_ptr.shape[0] - 1

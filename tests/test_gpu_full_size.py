@@ -163,3 +163,37 @@ def test_full_size_backward_receive(oracle):
                                       np.zeros(1, np.int64), np.zeros(1, np.int32), dim, want)
         assert np.array_equal(out1[r].view(np.uint32), want[0].view(np.uint32)), f"row {r}: {len(slots)} messages"
     _say(f"full size c4 backward receive: {len(rows)} rows ok, up to {counts.max()} messages per row")
+
+
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_full_size_fused_receive(oracle, name):
+    """The step whose marginal aggregation reads the receive buffer directly: the halo rows of the feature
+    matrix are never written, the output has the bits of the plain step, and sampled marginal rows agree
+    with the oracle run on the oracle's own de-quantised rows."""
+    cfg = CONFIGS[name]
+    _say(f"full size {name} fused receive: generating")
+    p = make_partition(cfg)
+    dim = cfg.dim
+    L = LayerStep(p, "cuda:0", seed=SEED)
+    L.run(B.SERIAL)
+    L.synchronize()
+    plain = L.out.cpu().numpy()
+    L.set_fused_receive(True)
+    L.feat[cfg.n_local: cfg.n_local + cfg.n_send] = float("nan")
+    L.out.fill_(float("nan"))
+    torch.cuda.synchronize()
+    _say(f"full size {name} fused receive: layer step")
+    L.run(B.ISOLATED)
+    L.synchronize()
+    out = L.out.cpu().numpy()
+    assert np.array_equal(out.view(np.uint32), plain.view(np.uint32))
+    assert bool(torch.isnan(L.feat[cfg.n_local: cfg.n_local + cfg.n_send]).all())
+    pl = L.plan
+    packed = L.recv_packed.cpu().numpy()[: pl.packed_bytes]
+    params = L.recv_params.cpu().numpy()[: pl.n]
+    H = p.feat.copy()
+    oracle.unpack_dequant(packed, params, pl.bits_host, pl.row_offset_host, pl.halo_idx_host, dim, H)
+    rng = np.random.default_rng(3)
+    rows = _sample_rows(rng, p.rowptr, *p.dependent_rows, 60)
+    worst = _check_rows(oracle, p, H, out, rows, dim)
+    _say(f"full size {name} fused receive: {len(rows)} rows ok, worst {worst:.3f} of tolerance")

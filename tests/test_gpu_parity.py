@@ -354,6 +354,94 @@ def test_spmm_c0_and_nonnegative_long_rows(oracle):
 
 
 # ------------------------------------------------------------------------------------------------------
+# aggregation that reads received rows straight from the receive buffer
+# ------------------------------------------------------------------------------------------------------
+
+def _packed_case(oracle, rng, n_cols, n_halo, dim, ldh, seed):
+    """Received rows for n_halo random columns: (halo, bits, off, packed, params, H_plain, H_ref) where H_plain
+    holds NaN in the received rows and H_ref holds what the oracle de-quantises there."""
+    halo = np.ascontiguousarray(rng.permutation(n_cols)[:n_halo], dtype=np.int32)
+    bits = rng.choice(np.array([2, 4, 8], dtype=np.uint8), size=n_halo)
+    peer = np.sort(rng.integers(0, 3, size=n_halo)).astype(np.int32)
+    perm, off, pbp = oracle.plan_layout(dim, bits, peer, 3)
+    bits = np.ascontiguousarray(bits[perm])
+    halo = np.ascontiguousarray(halo[perm])
+    src = (rng.standard_normal((n_halo, dim)) * rng.uniform(0.1, 3.0, size=(n_halo, 1))).astype(np.float32)
+    packed, params, _ = oracle.quantize_pack(src, dim, np.arange(n_halo, dtype=np.int32), bits, off, seed, int(pbp[-1]))
+    H_plain = np.full((n_cols, ldh), np.nan, dtype=np.float32)
+    H_plain[:, :dim] = rng.standard_normal((n_cols, dim), dtype=np.float32)
+    H_ref = H_plain[:, :dim].copy()
+    oracle.unpack_dequant(packed, params, bits, off, halo, dim, H_ref)
+    H_plain[halo] = np.nan                                  # the fused path must never read these rows
+    return halo, bits, off, packed, params, H_plain, H_ref
+
+
+def _gpu_spmm_packed(rowptr, col, val, rb, re, H, dim, slot_of_row, packed, params, bits, off, ldo):
+    out = torch.full((rowptr.shape[0] - 1, ldo), 7.0, dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(B.adaqp_spmm_workspace_bytes(re - rb, len(col), dim), 256), dtype=torch.uint8, device=DEV)
+    B.adaqp_spmm_csr_packed(torch.from_numpy(rowptr).to(DEV), torch.from_numpy(col).to(DEV),
+                            torch.from_numpy(val).to(DEV), rb, re, torch.from_numpy(H).to(DEV), dim, out,
+                            torch.from_numpy(slot_of_row).to(DEV), torch.from_numpy(packed).to(DEV),
+                            torch.from_numpy(params).to(DEV), torch.from_numpy(bits).to(DEV),
+                            torch.from_numpy(off).to(DEV), ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("dim,ldh", [(128, 128), (602, 608), (602, 602), (300, 300), (7, 7), (1, 1), (66, 66),
+                                     (130, 132), (250, 256), (2049, 2080), (2304, 2304), (4100, 4100), (515, 515)])
+def test_spmm_packed_rows(oracle, dim, ldh):
+    _say(f"spmm from packed rows dim={dim} ldh={ldh}")
+    rng = np.random.default_rng(1000 + dim)
+    n_rows, n_cols, n_halo = 500, 700, 330
+    degs = rng.integers(0, 12, size=n_rows)
+    degs[10] = 650                                                     # split over several pieces
+    degs[300:310] = 0
+    rowptr, col, val = _random_graph(rng, n_rows, n_cols, degs)
+    halo, bits, off, packed, params, H_plain, H_ref = _packed_case(oracle, rng, n_cols, n_halo, dim, ldh, seed=77)
+    slot_of_row = B.adaqp_plan_slot_of_row(n_cols, halo)
+    assert np.array_equal(np.nonzero(slot_of_row >= 0)[0], np.sort(halo))
+    assert np.array_equal(halo[slot_of_row[np.sort(halo)]], np.sort(halo))
+    ldo = ldh if ldh % 32 == 0 else dim
+    got = _gpu_spmm_packed(rowptr, col, val, 0, n_rows, H_plain, dim, slot_of_row, packed, params, bits, off, ldo)
+    want, mag = oracle.spmm_csr(rowptr, col, val, 0, n_rows, H_ref, dim)
+    err = np.abs(got[:, :dim].astype(np.float64) - want)
+    worst = float((err / (SPMM_RTOL * mag + 1e-30)).max())
+    assert worst <= 1.0, f"worst error {worst:.3f} x tolerance"
+    zero_to = _padded_cols(dim, ldo) if (ldo % 32 == 0 and ldh % 32 == 0) else dim
+    assert np.all(got[:, dim:zero_to] == 0.0) and np.all(got[:, zero_to:] == 7.0)
+    # bit-identical to de-quantising into H first (same arithmetic, same order)
+    H_filled = np.full((n_cols, ldh), np.nan, dtype=np.float32)
+    H_filled[:, :dim] = H_ref
+    unfused = _gpu_spmm(rowptr, col, val, 0, n_rows, H_filled, dim, ldo=ldo)
+    assert np.array_equal(got.view(np.uint32), unfused.view(np.uint32))
+    # a sub-range, and a map with unusable slots: those entries read H
+    sub = _gpu_spmm_packed(rowptr, col, val, 9, 12, H_plain, dim, slot_of_row, packed, params, bits, off, ldo)
+    sub_unfused = _gpu_spmm(rowptr, col, val, 9, 12, H_filled, dim, ldo=ldo)      # same pieces, same order
+    assert np.array_equal(sub.view(np.uint32), sub_unfused.view(np.uint32)) and np.all(sub[:9] == 7.0)
+    broken = slot_of_row.copy()
+    broken[halo[:50]] = n_halo + 5
+    H_mixed = H_plain.copy()
+    H_mixed[halo[:50], :dim] = H_ref[halo[:50]]
+    again = _gpu_spmm_packed(rowptr, col, val, 0, n_rows, H_mixed, dim, broken, packed, params, bits, off, ldo)
+    assert np.array_equal(again.view(np.uint32), got.view(np.uint32))
+
+
+def test_spmm_packed_argument_checks():
+    z = torch.zeros(64, dtype=torch.uint8, device=DEV)
+    rowptr = torch.zeros(2, dtype=torch.int64, device=DEV)
+    col = torch.zeros(1, dtype=torch.int32, device=DEV)[:0]
+    val = torch.zeros(1, dtype=torch.float32, device=DEV)[:0]
+    H = torch.zeros((4, 32), dtype=torch.float32, device=DEV)
+    out = torch.zeros((1, 32), dtype=torch.float32, device=DEV)
+    slot = torch.full((4,), -1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(4096, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.AdaqpError):                      # a map without slots
+        B.adaqp_spmm_csr_packed(rowptr, col, val, 0, 1, H, 32, out, slot, z, torch.zeros((1, 2), device=DEV),
+                                z[:0], torch.zeros(1, dtype=torch.int64, device=DEV)[:0], ws)
+
+
+# ------------------------------------------------------------------------------------------------------
 # the layer step
 # ------------------------------------------------------------------------------------------------------
 
@@ -435,3 +523,28 @@ def test_layer_step_matches_oracle_in_every_schedule(oracle, name):
             L2.synchronize()
             assert np.array_equal(L2.out.cpu().numpy().view(np.uint32), want_out.view(np.uint32)), \
                 f"schedule {schedule}: backward receive differs"
+
+
+def test_layer_step_fused_receive(oracle):
+    """Forward step whose dependent aggregation reads the receive buffer: same output bits as the step that
+    de-quantises into the feature matrix first, and the halo rows of the feature matrix stay untouched."""
+    p = make_partition(CONFIGS["c0"])
+    cfg = p.cfg
+    seed = 1234
+    _, _, _, out64, mag = _oracle_layer(oracle, p, seed)
+    plain = LayerStep(p, DEV, seed=seed)
+    plain.run(B.SERIAL)
+    plain.synchronize()
+    want = plain.out.cpu().numpy()
+    for schedule in (B.SERIAL, B.ISOLATED, B.FREE):
+        L = LayerStep(p, DEV, seed=seed, fused_receive=True)
+        L.feat[cfg.n_local: cfg.n_local + cfg.n_send] = float("nan")
+        L.out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        L.run(schedule)
+        L.synchronize()
+        out = L.out.cpu().numpy()
+        assert np.all(np.abs(out.astype(np.float64) - out64) <= SPMM_RTOL * mag + 1e-30)
+        assert np.array_equal(out.view(np.uint32), want.view(np.uint32)), f"schedule {schedule}"
+        assert bool(torch.isnan(L.feat[cfg.n_local: cfg.n_local + cfg.n_send]).all())
+        assert np.array_equal(L.recv_packed.cpu().numpy(), plain.recv_packed.cpu().numpy())

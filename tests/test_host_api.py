@@ -122,3 +122,14 @@ def test_plan_recv_segments():
     for g in range(len(seg_ptr) - 1):
         seg = order[seg_ptr[g]: seg_ptr[g + 1]]
         assert len(set(dst[seg].tolist())) == 1 and np.all(np.diff(seg) > 0)
+
+
+def test_plan_slot_of_row():
+    halo = np.array([7, 3, 9, 4], dtype=np.int32)
+    m = B.adaqp_plan_slot_of_row(10, halo)
+    assert m.dtype == np.int32 and m.tolist() == [-1, -1, -1, 1, 3, -1, -1, 0, -1, 2]
+    assert B.adaqp_plan_slot_of_row(3, np.zeros(0, np.int32)).tolist() == [-1, -1, -1]
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_plan_slot_of_row(10, np.array([1, 1], dtype=np.int32))       # a row listed twice
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_plan_slot_of_row(10, np.array([10], dtype=np.int32))         # out of range
