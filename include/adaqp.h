@@ -193,6 +193,24 @@ int adaqp_spmm_csr(const int64_t *rowptr_dev, const int32_t *col_dev, const floa
                    float *out_dev, int64_t ldo,
                    void *workspace_dev, int64_t workspace_bytes, void *stream);
 
+/* Host only: bit-widths for the next period from the traced beta values (Sec. 4.2).  Per device pair the
+ * messages are sorted by descending beta (ties: ascending slot) and cut into groups of group_size that share a
+ * width (the last group of a pair may be shorter).  The widths minimise, over the assignments a greedy search
+ * visits, Eq. 9:  lambda * sum_k beta_k / (2^b_k - 1)^2  +  (1 - lambda) * max_i (theta_i * dim * sum_{k in i} b_k
+ * + gamma_i), pairs without messages left out of the maximum.  The paper solves the same problem with a MILP
+ * solver; the search here starts at 2 bits everywhere, orders a pair's upgrades (2->4, 4->8) by variance
+ * removed per extra bit, and for every pair time such a prefix can reach lets each pair take the longest prefix
+ * that fits under it (exact for one pair; within one upgrade's gain per pair otherwise).
+ *   beta_host [n] float >= 0 (adaqp_quantize_pack_trace's output, copied to the host);  peer_of_slot_host [n];
+ *   theta_host, gamma_host [n_peers]: cost model of Eq. 7, seconds per bit (>= 0) and seconds;
+ *   bits_out [n]: 2, 4 or 8;  objective_out: NULL or [3] = {Eq. 9 value, Eq. 8 variance, largest pair time} of
+ *   the result, evaluated from their definitions.
+ * Errors: EINVAL (negative or non-finite beta / theta, peer out of range, lambda outside [0, 1],
+ * group_size <= 0), ESIZE. */
+int adaqp_assign_bits(int64_t n, const float *beta_host, const int32_t *peer_of_slot_host, int32_t n_peers,
+                      int32_t dim, int32_t group_size, double lambda, const double *theta_host,
+                      const double *gamma_host, uint8_t *bits_out, double *objective_out);
+
 /* Host only: inverse of halo_idx.  slot_of_row_out[n_rows] = t for the row halo_idx_host[t], -1 for every
  * other row.  Errors: EINVAL (index out of range, a row listed twice), ESIZE (n > 2^31 - 1). */
 int adaqp_plan_slot_of_row(int64_t n_rows, int64_t n, const int32_t *halo_idx_host, int32_t *slot_of_row_out);

@@ -76,6 +76,7 @@ _SIGNATURES = {
     "adaqp_spmm_workspace_bytes": (ctypes.c_int, [_i64, _i64, _i32, ctypes.POINTER(_i64)]),
     "adaqp_spmm_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
                                       _vp, _i64, _vp, _i64, _vp]),
+    "adaqp_assign_bits": (ctypes.c_int, [_i64, _vp, _vp, _i32, _i32, _i32, ctypes.c_double, _vp, _vp, _vp, _vp]),
     "adaqp_plan_slot_of_row": (ctypes.c_int, [_i64, _i64, _vp, _vp]),
     "adaqp_spmm_csr_packed": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
                                              _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
@@ -245,6 +246,24 @@ def adaqp_spmm_csr(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, r
                                 hp, n_cols, ldh, dim, op, ldo, _dev(workspace, torch.uint8, "workspace"),
                                 workspace.numel(), _stream(stream)),
            "adaqp_spmm_csr")
+
+
+def adaqp_assign_bits(beta_host: np.ndarray, peer_of_slot_host: np.ndarray, n_peers: int, dim: int,
+                      group_size: int, lam: float, theta: np.ndarray, gamma: np.ndarray
+                      ) -> Tuple[np.ndarray, np.ndarray]:
+    """Host-only.  Returns (bits uint8[n], float64[3] = Eq. 9 value, variance, largest pair time)."""
+    beta = np.ascontiguousarray(beta_host, dtype=np.float32)
+    peer = np.ascontiguousarray(peer_of_slot_host, dtype=np.int32)
+    theta = np.ascontiguousarray(theta, dtype=np.float64)
+    gamma = np.ascontiguousarray(gamma, dtype=np.float64)
+    if theta.shape[0] != n_peers or gamma.shape[0] != n_peers or peer.shape[0] != beta.shape[0]:
+        raise ValueError("theta / gamma need n_peers entries, peer_of_slot one per beta")
+    bits = np.zeros(beta.shape[0], dtype=np.uint8)
+    obj = np.zeros(3, dtype=np.float64)
+    _check(lib().adaqp_assign_bits(beta.shape[0], beta.ctypes.data, peer.ctypes.data, n_peers, dim, group_size,
+                                   float(lam), theta.ctypes.data, gamma.ctypes.data, bits.ctypes.data,
+                                   obj.ctypes.data), "adaqp_assign_bits")
+    return bits, obj
 
 
 def adaqp_plan_slot_of_row(n_rows: int, halo_idx_host: np.ndarray) -> np.ndarray:

@@ -35,6 +35,7 @@ class PartitionConfig:
     seed: int = 0
     draw_inflation: float = 1.0  # extra draws to make up for duplicates removed per row
     stands_in_for: str = ""
+    aggregator: str = "gcn"     # coefficients: "gcn" symmetric normalisation | "mean" (GraphSAGE-style, 1 / row degree)
 
 
 # Zipf(1.5) samples are clipped at this raw value; with the clipped mean (about 170) the largest degree
@@ -153,7 +154,13 @@ def _forward_graph(rng: np.random.Generator, cfg: PartitionConfig):
     d_col = np.empty(n_cols, dtype=np.float64)
     d_col[:n_local] = d_row
     d_col[n_local:] = 1.0 + np.bincount(cols_u[cols_u >= n_local] - n_local, minlength=n_halo)
-    val = (1.0 / np.sqrt(d_row[rows_u] * d_col[cols_u])).astype(np.float32)
+    if cfg.aggregator == "gcn":
+        val = (1.0 / np.sqrt(d_row[rows_u] * d_col[cols_u])).astype(np.float32)
+    elif cfg.aggregator == "mean":
+        # mean aggregator (Sec. 5 trains GraphSAGE with it): every neighbour of a row, itself included, weighs 1/d~
+        val = (1.0 / d_row[rows_u]).astype(np.float32)
+    else:
+        raise ValueError(cfg.aggregator)
     return rowptr, cols_u, val, n_central, n_cols
 
 

@@ -548,3 +548,58 @@ def test_layer_step_fused_receive(oracle):
         assert np.array_equal(out.view(np.uint32), want.view(np.uint32)), f"schedule {schedule}"
         assert bool(torch.isnan(L.feat[cfg.n_local: cfg.n_local + cfg.n_send]).all())
         assert np.array_equal(L.recv_packed.cpu().numpy(), plain.recv_packed.cpu().numpy())
+
+
+def test_mean_aggregator_layer_step(oracle):
+    """GraphSAGE-style mean coefficients (1 / row degree) through the same step."""
+    p = make_partition(replace(CONFIGS["c0"], aggregator="mean"))
+    _, _, feat_w, out64, mag = _oracle_layer(oracle, p, 9)
+    L = LayerStep(p, DEV, seed=9)
+    L.out.fill_(float("nan"))
+    L.run(B.ISOLATED)
+    L.synchronize()
+    out = L.out.cpu().numpy()
+    assert np.all(np.abs(out.astype(np.float64) - out64) <= SPMM_RTOL * mag + 1e-30)
+    assert np.array_equal(L.feat.cpu().numpy().view(np.uint32), feat_w.view(np.uint32))
+    # a mean of values stays inside their range
+    lo, hi = feat_w.min(), feat_w.max()
+    assert out.min() >= lo - 1e-4 and out.max() <= hi + 1e-4
+
+
+def test_trace_assign_replan_loop(oracle):
+    """One period of Sec. 3.3: the step traces beta, the assigner turns it into widths, the next step runs with
+    the new layout.  The oracle does the same from its own trace; widths and bytes must agree exactly."""
+    import dataclasses
+    from oracle import assigner as A
+    p = make_partition(CONFIGS["c0"])
+    cfg = p.cfg
+    seed = 77
+    L = LayerStep(p, DEV, seed=seed)
+    L.run(B.SERIAL)
+    L.synchronize()
+    pl = L.plan
+    beta_gpu = L.beta.cpu().numpy()
+    peer_sorted = np.ascontiguousarray(p.peer_of_slot[pl.perm])
+    theta = np.array([1.0, 1.5, 0.7]) * 1e-8
+    gamma = np.full(cfg.n_peers, 1e-5)
+    lam, group = 1e-7, 20
+    bits_sorted, obj = B.adaqp_assign_bits(beta_gpu, peer_sorted, cfg.n_peers, cfg.dim, group, lam, theta, gamma)
+    beta_cpu = oracle.trace_beta(p.feat, cfg.dim, pl.send_idx_host, L.alpha_sq_host)
+    want_bits = A.greedy(beta_cpu, peer_sorted, cfg.n_peers, cfg.dim, group, lam, theta, gamma)
+    assert np.array_equal(bits_sorted, want_bits)
+    assert set(np.unique(bits_sorted)) == {2, 4, 8}
+    f, _, _ = A.objective(beta_cpu, peer_sorted, cfg.n_peers, cfg.dim, bits_sorted, lam, theta, gamma)
+    assert obj[0] == pytest.approx(f, rel=1e-12)
+    # the assignment beats the one it replaces on the objective it was chosen for
+    f_old, _, _ = A.objective(beta_cpu, peer_sorted, cfg.n_peers, cfg.dim, pl.bits_host, lam, theta, gamma)
+    assert f < f_old
+    bits_new = np.zeros_like(p.bits)
+    bits_new[pl.perm] = bits_sorted                                  # back to the caller's slot order
+    p2 = dataclasses.replace(p, bits=bits_new)
+    packed_w, params_w, feat_w, out64, mag = _oracle_layer(oracle, p2, seed)
+    L2 = LayerStep(p2, DEV, seed=seed)
+    L2.run(B.ISOLATED)
+    L2.synchronize()
+    assert np.array_equal(L2.recv_packed.cpu().numpy()[: L2.plan.packed_bytes], packed_w)
+    assert np.array_equal(L2.feat.cpu().numpy().view(np.uint32), feat_w.view(np.uint32))
+    assert np.all(np.abs(L2.out.cpu().numpy().astype(np.float64) - out64) <= SPMM_RTOL * mag + 1e-30)

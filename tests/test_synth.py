@@ -59,3 +59,12 @@ def test_backward_partition_is_the_transpose():
         rows = p.halo_idx[p.peer_of_slot == peer]
         assert len(set(rows.tolist())) == len(rows)
     assert len(set(p.halo_idx.tolist())) < 500
+
+
+def test_mean_aggregator_rows_sum_to_one():
+    from dataclasses import replace
+    p = make_partition(replace(CONFIGS["c0"], aggregator="mean"))
+    sums = np.add.reduceat(p.val.astype(np.float64), p.rowptr[:-1])
+    assert np.allclose(sums, 1.0, atol=1e-5)
+    q = make_partition(CONFIGS["c0"])
+    assert np.array_equal(p.col, q.col) and not np.array_equal(p.val, q.val)
