@@ -232,6 +232,35 @@ int adaqp_spmm_csr_packed(const int64_t *rowptr_dev, const int32_t *col_dev, con
                           void *workspace_dev, int64_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------------- */
+/* Aggregation for graphs with long rows (mean degree in the hundreds, as the densest dataset of Sec. 5):
+ * the same sum as adaqp_spmm_csr (Sec. 2.1 Eq. 3), scheduled so that each of the GPU's ADAQP_SPMM_TILES L2
+ * caches keeps re-using one range of the rows of H.  The graph's columns are cut into ADAQP_SPMM_TILES ranges
+ * with equal entry counts, once per graph, on the host.  Line-padded layout only. */
+#define ADAQP_SPMM_TILES 8
+
+/* Host only.  For rows [row_begin, row_end) of a host CSR whose rows list ascending, distinct, in-range
+ * columns: col_bounds_out[ADAQP_SPMM_TILES + 1] (0 = bounds[0] <= ... <= bounds[TILES] = n_cols) and
+ * tile_off_out[(row_end - row_begin) * (ADAQP_SPMM_TILES + 1)]: entry t of a row = number of its entries with
+ * column < bounds[t].  Errors: EINVAL (unsorted / repeated / out-of-range column, bad rowptr). */
+int adaqp_plan_spmm_tiles(const int64_t *rowptr_host, const int32_t *col_host, int64_t row_begin, int64_t row_end,
+                          int64_t n_cols, int32_t *col_bounds_out, int32_t *tile_off_out);
+
+/* Bytes of workspace adaqp_spmm_csr_tiled needs for n_rows rows (one partial row per tile). */
+int adaqp_spmm_tiled_workspace_bytes(int64_t n_rows, int32_t dim, int64_t *bytes_out);
+
+/* out[r, 0:dim] = sum_j val[j] * H[col[j], 0:dim] for r in [row_begin, row_end), like adaqp_spmm_csr.
+ * tile_off_dev: device copy of adaqp_plan_spmm_tiles' table for the same row range.  Entries whose column is
+ * out of range are skipped; a table that disagrees with rowptr is clamped to the row (wrong sums, no stray
+ * access).  The summation order is fixed by the table and the launch geometry: runs are bit-identical.
+ * H and out must be line-padded (pitch a multiple of 32 floats, base 128-byte aligned); the padding of the
+ * written rows is set to zero.  workspace_dev: 256-byte aligned, >= adaqp_spmm_tiled_workspace_bytes.
+ * Errors: EINVAL (layout, alignment, null), ESIZE (workspace too small, too many rows), EHIP. */
+int adaqp_spmm_csr_tiled(const int64_t *rowptr_dev, const int32_t *col_dev, const float *val_dev, int64_t nnz,
+                         int64_t row_begin, int64_t row_end, const float *H_dev, int64_t n_cols, int64_t ldh,
+                         int32_t dim, float *out_dev, int64_t ldo, const int32_t *tile_off_dev,
+                         void *workspace_dev, int64_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------------- */
 /* One layer's aggregation step with the message path overlapped (Sec. 3.1, Sec. 3.4 Fig. 7).             */
 /* ---------------------------------------------------------------------------------------------------- */
 
@@ -278,6 +307,12 @@ typedef struct adaqp_layer_desc {
     const int32_t *slot_of_row_dev; /* forward only, optional: adaqp_plan_slot_of_row of halo_idx.  If given, the
                                        received rows are NOT de-quantised into feat; the dependent aggregation
                                        reads them from the receive buffer (adaqp_spmm_csr_packed) */
+    const int32_t *tile_off_overlap_dev;    /* optional: adaqp_plan_spmm_tiles of the overlap / dependent row range. */
+    const int32_t *tile_off_dependent_dev;  /* If given, that range is aggregated by adaqp_spmm_csr_tiled (line-padded
+                                               layout required; the range's workspace must then hold
+                                               adaqp_spmm_tiled_workspace_bytes as well).  With a table for the
+                                               dependent range, slot_of_row_dev is ignored: the received rows are
+                                               de-quantised into feat */
     const int32_t *recv_seg_order_dev;  /* backward only, optional: adaqp_plan_recv_segments of halo_idx */
     const int64_t *recv_seg_ptr_dev;
     int64_t n_recv_seg;

@@ -46,6 +46,7 @@ class LayerDesc(ctypes.Structure):
         ("send_idx_dev", _vp), ("bits_dev", _vp), ("row_offset_dev", _vp), ("halo_idx_dev", _vp),
         ("recv_order_dev", _vp),
         ("slot_of_row_dev", _vp),
+        ("tile_off_overlap_dev", _vp), ("tile_off_dependent_dev", _vp),
         ("recv_seg_order_dev", _vp), ("recv_seg_ptr_dev", _vp), ("n_recv_seg", _i64),
         ("n_send", _i64), ("seed", _u64),
         ("packed_dev", _vp), ("params_dev", _vp), ("alpha_sq_dev", _vp), ("beta_dev", _vp),
@@ -76,6 +77,10 @@ _SIGNATURES = {
     "adaqp_spmm_workspace_bytes": (ctypes.c_int, [_i64, _i64, _i32, ctypes.POINTER(_i64)]),
     "adaqp_spmm_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
                                       _vp, _i64, _vp, _i64, _vp]),
+    "adaqp_plan_spmm_tiles": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i64, _vp, _vp]),
+    "adaqp_spmm_tiled_workspace_bytes": (ctypes.c_int, [_i64, _i32, _vp]),
+    "adaqp_spmm_csr_tiled": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _i64, _i32, _vp, _i64,
+                                            _vp, _vp, _i64, _vp]),
     "adaqp_assign_bits": (ctypes.c_int, [_i64, _vp, _vp, _i32, _i32, _i32, ctypes.c_double, _vp, _vp, _vp, _vp]),
     "adaqp_plan_slot_of_row": (ctypes.c_int, [_i64, _i64, _vp, _vp]),
     "adaqp_spmm_csr_packed": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
@@ -246,6 +251,39 @@ def adaqp_spmm_csr(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, r
                                 hp, n_cols, ldh, dim, op, ldo, _dev(workspace, torch.uint8, "workspace"),
                                 workspace.numel(), _stream(stream)),
            "adaqp_spmm_csr")
+
+
+SPMM_TILES = 8
+
+
+def adaqp_plan_spmm_tiles(rowptr_host: np.ndarray, col_host: np.ndarray, row_begin: int, row_end: int,
+                          n_cols: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Host-only.  Returns (col_bounds int32[9], tile_off int32[rows, 9])."""
+    rowptr = np.ascontiguousarray(rowptr_host, dtype=np.int64)
+    col = np.ascontiguousarray(col_host, dtype=np.int32)
+    bounds = np.zeros(SPMM_TILES + 1, dtype=np.int32)
+    off = np.zeros((max(row_end - row_begin, 0), SPMM_TILES + 1), dtype=np.int32)
+    _check(lib().adaqp_plan_spmm_tiles(rowptr.ctypes.data, col.ctypes.data, row_begin, row_end, n_cols,
+                                       bounds.ctypes.data, off.ctypes.data), "adaqp_plan_spmm_tiles")
+    return bounds, off
+
+
+def adaqp_spmm_tiled_workspace_bytes(n_rows: int, dim: int) -> int:
+    out = ctypes.c_int64(0)
+    _check(lib().adaqp_spmm_tiled_workspace_bytes(n_rows, dim, ctypes.byref(out)), "adaqp_spmm_tiled_workspace_bytes")
+    return int(out.value)
+
+
+def adaqp_spmm_csr_tiled(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, row_begin: int, row_end: int,
+                         H: torch.Tensor, dim: int, out: torch.Tensor, tile_off: torch.Tensor,
+                         workspace: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    hp, n_cols, ldh = _matrix(H, "H")
+    op, _, ldo = _matrix(out, "out")
+    _check(lib().adaqp_spmm_csr_tiled(_dev(rowptr, torch.int64, "rowptr"), _dev(col, torch.int32, "col"),
+                                      _dev(val, torch.float32, "val"), col.numel(), row_begin, row_end,
+                                      hp, n_cols, ldh, dim, op, ldo, _dev(tile_off, torch.int32, "tile_off"),
+                                      _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                      _stream(stream)), "adaqp_spmm_csr_tiled")
 
 
 def adaqp_assign_bits(beta_host: np.ndarray, peer_of_slot_host: np.ndarray, n_peers: int, dim: int,

@@ -174,7 +174,8 @@ int check_desc(const adaqp_layer_desc *d)
 
 bool fused_receive(const adaqp_layer_desc *d)
 {
-    return d->direction == ADAQP_FORWARD && d->slot_of_row_dev && d->n_send > 0 && d->packed_bytes >= 4;
+    return d->direction == ADAQP_FORWARD && d->slot_of_row_dev && !d->tile_off_dependent_dev && d->n_send > 0 &&
+           d->packed_bytes >= 4;
 }
 
 int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
@@ -184,6 +185,10 @@ int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
     const int64_t nz = overlap_part ? d->overlap_nnz : d->dependent_nnz;
     void *ws = overlap_part ? d->workspace_overlap_dev : d->workspace_dependent_dev;
     const int64_t wsb = overlap_part ? d->workspace_overlap_bytes : d->workspace_dependent_bytes;
+    const int32_t *tile_off = overlap_part ? d->tile_off_overlap_dev : d->tile_off_dependent_dev;
+    if (tile_off)
+        return adaqp_spmm_csr_tiled(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, d->feat_dev, d->n_feat_rows,
+                                    d->ld, d->dim, d->out_dev, d->ldo, tile_off, ws, wsb, st);
     if (!overlap_part && fused_receive(d))
         return adaqp_spmm_csr_packed(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, nz, d->feat_dev,
                                      d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, d->slot_of_row_dev,

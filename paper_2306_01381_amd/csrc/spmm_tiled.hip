@@ -1,0 +1,318 @@
+// Neighbour aggregation (Sec. 2.1 Eq. 3: out[v] = sum_u alpha(u, v) * H[u]) for graphs whose rows are long
+// enough that every row of H is used hundreds of times - the regime of the paper's densest dataset (mean
+// degree near 500), where the merge-path kernel streams the same 240 MB operand 290 times.
+//
+// MI355X has eight XCDs with a private 4 MB L2 each, and workgroups are dealt to XCDs round-robin.  The columns
+// of the graph are cut into eight ranges ("tiles", equal entry counts, planned on the host once per graph) and
+// the feature columns into chunks of 64 or 128; workgroup i works on tile i mod 8, so an XCD only ever touches
+// one tile's rows of H, and with the chunk index outermost its working set at any time is one tile x one chunk:
+// a few MB that stay in its L2.  A gather of that shape runs at about 25 TB/s on this part against 8-9 TB/s
+// when the same rows come through the fabric.  The price: every (row, tile) segment leaves a partial sum in a
+// workspace, added up in tile order by a second kernel (deterministic), and the entries are re-read once per chunk.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <vector>
+
+#include "adaqp.h"
+#include "common.hpp"
+
+namespace adaqp {
+namespace {
+
+constexpr int kTiles = ADAQP_SPMM_TILES;
+
+struct TiledArgs {
+    const int64_t *rowptr;      // already offset to row_begin: rowptr[0..n_rows]
+    const int32_t *col;
+    const float *val;
+    int64_t nnz;
+    int32_t n_rows;
+    const int32_t *tile_off;    // [n_rows][kTiles + 1]: entries of the row that precede each tile
+    const float *H;
+    int64_t n_cols, ldh;
+    int32_t dim, wdim;          // wdim = dim rounded up to whole 128-byte lines
+    float *out;                 // already offset to row_begin
+    int64_t ldo;
+    float *partial;             // [kTiles][n_rows][wdim]
+    uint32_t n_row_blocks;
+    int32_t rows_per_wave;
+};
+
+__device__ __forceinline__ int32_t uniform_i32(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__device__ __forceinline__ int64_t clamp64(int64_t v, int64_t lo, int64_t hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+// Entries of row r that fall into `tile`, clamped so that a corrupt plan or rowptr cannot lead outside the arrays.
+__device__ __forceinline__ void segment(const TiledArgs &a, int64_t r, int tile, int64_t *first, int32_t *count)
+{
+    const int64_t lo = clamp64(a.rowptr[r], 0, a.nnz);
+    const int64_t hi = clamp64(a.rowptr[r + 1], lo, a.nnz);
+    const int32_t *off = a.tile_off + r * (kTiles + 1) + tile;
+    const int64_t s = clamp64(lo + off[0], lo, hi);
+    const int64_t e = clamp64(lo + off[1], s, hi);
+    const int64_t n = e - s;
+    *first = s;
+    *count = n > 0x7FFFFFFF ? 0x7FFFFFFF : (int32_t)n;
+}
+
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void store4_streaming(float *p, const float *v)
+{
+    float4_t x = {v[0], v[1], v[2], v[3]};
+    __builtin_nontemporal_store(x, reinterpret_cast<float4_t *>(p));
+}
+
+__device__ __forceinline__ void load4_streaming(const float *p, float *v)
+{
+    const float4_t x = __builtin_nontemporal_load(reinterpret_cast<const float4_t *>(p));
+    v[0] = x[0];
+    v[1] = x[1];
+    v[2] = x[2];
+    v[3] = x[3];
+}
+
+__device__ __forceinline__ int32_t shuffle_i32(int32_t v, int src_lane)
+{
+    return __builtin_amdgcn_ds_bpermute(src_lane << 2, v);
+}
+
+__device__ __forceinline__ float shuffle_f32(float v, int src_lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src_lane << 2, __builtin_bit_cast(int32_t, v)));
+}
+
+// LPE lanes share one entry (each lane four columns): 16 -> chunks of 64 columns, 32 -> chunks of 128.
+// A wave has 64 / LPE entries in each load instruction and U such loads in flight.
+template <int LPE, int U>
+__global__ __launch_bounds__(kBlock) void spmm_tiled_kernel(const TiledArgs a)
+{
+    constexpr int SLOTS = kWave / LPE;
+    constexpr int CW = LPE * 4;
+    static_assert(LPE % U == 0, "a batch of 64 entries is LPE load steps: a whole number of U-step groups");
+    const int lane = threadIdx.x & (kWave - 1);
+    const int q = lane / LPE, l = lane % LPE;
+    // the tile is the fastest-running index: consecutive workgroups land on consecutive XCDs
+    const uint32_t tile = blockIdx.x % kTiles;
+    const uint32_t rest = blockIdx.x / kTiles;
+    const uint32_t rb = rest % a.n_row_blocks;
+    const uint32_t chunk = rest / a.n_row_blocks;
+    const int32_t c0 = (int32_t)chunk * CW + l * 4;
+    const bool live = c0 < a.wdim;                          // wdim is a multiple of 32: a live vector is whole
+    const int wave = threadIdx.x >> 6;
+    const int64_t r_begin = ((int64_t)rb * kWavesPerBlock + wave) * a.rows_per_wave;
+    const int64_t r_end = r_begin + a.rows_per_wave < a.n_rows ? r_begin + a.rows_per_wave : a.n_rows;
+    const float *hbase = a.H + (live ? c0 : 0);
+
+    for (int64_t r = r_begin; r < r_end; ++r) {
+        int64_t first;
+        int32_t count;
+        segment(a, r, (int)tile, &first, &count);
+        first = (int64_t)(((uint64_t)(uint32_t)uniform_i32((int32_t)(first >> 32)) << 32) |
+                          (uint32_t)uniform_i32((int32_t)first));
+        count = uniform_i32(count);
+        if (count == 0) continue;                           // the reduction skips this partial as well
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int32_t j = 0; j < count; j += kWave) {
+            const int32_t nb = count - j < kWave ? count - j : kWave;
+            // lane i holds entry j + i.  A lane without an entry, or with an out-of-range column, holds the
+            // complement of a column that is safe to read (negative): the row is fetched and then dropped
+            const int32_t mine = lane < nb ? lane : 0;
+            int32_t my_col = __builtin_nontemporal_load(a.col + first + j + mine);
+            const float my_val = __builtin_nontemporal_load(a.val + first + j + mine);
+            if (my_col < 0 || my_col >= a.n_cols) my_col = ~0;
+            else if (lane >= nb) my_col = ~my_col;
+            const int32_t n_it = (nb + SLOTS - 1) / SLOTS;
+            for (int32_t it = 0; it < n_it; it += U) {
+                float h[U][4];
+                float alpha[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    // (it + u) * SLOTS + q <= 63: n_it <= 64 / SLOTS, which is a multiple of U
+                    const int e = ((it + u) * SLOTS + q) & (kWave - 1);
+                    const int32_t c = shuffle_i32(my_col, e);
+                    alpha[u] = shuffle_f32(my_val, e);
+                    const bool use = c >= 0 && live;
+                    const int32_t row = c ^ (c >> 31);                  // c if c >= 0, else ~c
+                    float4 x = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    if (use) x = *reinterpret_cast<const float4 *>(hbase + (int64_t)row * a.ldh);   // masked lanes: no traffic
+                    h[u][0] = x.x;
+                    h[u][1] = x.y;
+                    h[u][2] = x.z;
+                    h[u][3] = x.w;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) acc[k] = fmaf(alpha[u], h[u][k], acc[k]);
+            }
+        }
+        // the SLOTS partial sums of the row, combined pairwise in a fixed order
+#pragma unroll
+        for (int step = LPE; step < kWave; step <<= 1)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[k] += shuffle_f32(acc[k], lane ^ step);
+        if (q == 0 && live) {
+            store4_streaming(a.partial + ((int64_t)tile * a.n_rows + r) * a.wdim + c0, acc);
+        }
+    }
+}
+
+// out[r] = sum over the tiles that hold entries of row r, in tile order; whole lines, row padding zero.
+__global__ __launch_bounds__(kBlock) void spmm_tiled_reduce_kernel(const TiledArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t r = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (r >= a.n_rows) return;
+    uint32_t present = 0;
+    for (int t = 0; t < kTiles; ++t) {
+        int64_t first;
+        int32_t count;
+        segment(a, r, t, &first, &count);
+        if (count > 0) present |= 1u << t;
+    }
+    present = (uint32_t)uniform_i32((int32_t)present);
+    float *o = a.out + r * a.ldo;
+    for (int32_t c = lane * 4; c < a.wdim; c += kWave * 4) {
+        float x[kTiles][4];
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t) {
+            if (present & (1u << t)) {
+                load4_streaming(a.partial + ((int64_t)t * a.n_rows + r) * a.wdim + c, x[t]);
+            } else {
+                x[t][0] = x[t][1] = x[t][2] = x[t][3] = 0.0f;
+            }
+        }
+        float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t)
+            if (present & (1u << t))
+#pragma unroll
+                for (int k = 0; k < 4; ++k) sum[k] += x[t][k];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (c + k >= a.dim) sum[k] = 0.0f;              // row padding
+        store4_streaming(o + c, sum);
+    }
+}
+
+int64_t tiled_bytes(int64_t n_rows, int32_t dim)
+{
+    const int64_t wdim = ((int64_t)dim + 31) / 32 * 32;
+    return ((int64_t)kTiles * n_rows * wdim * 4 + 255) / 256 * 256;
+}
+
+}  // namespace
+}  // namespace adaqp
+
+using namespace adaqp;
+
+extern "C" int adaqp_plan_spmm_tiles(const int64_t *rowptr_host, const int32_t *col_host, int64_t row_begin,
+                                     int64_t row_end, int64_t n_cols, int32_t *col_bounds_out,
+                                     int32_t *tile_off_out)
+{
+    if (row_begin < 0 || row_end < row_begin || n_cols < 0 || n_cols > INT32_MAX) return ADAQP_EINVAL;
+    if (!rowptr_host || !col_bounds_out) return ADAQP_EINVAL;
+    const int64_t n_rows = row_end - row_begin;
+    if (n_rows > 0 && !tile_off_out) return ADAQP_EINVAL;
+    const int64_t e0 = rowptr_host[row_begin], e1 = rowptr_host[row_end];
+    if (e0 < 0 || e1 < e0) return ADAQP_EINVAL;
+    if (e1 > e0 && !col_host) return ADAQP_EINVAL;
+    // entries per column, then boundaries at equal entry counts
+    std::vector<int64_t> uses((size_t)n_cols + 1, 0);
+    for (int64_t r = row_begin; r < row_end; ++r) {
+        const int64_t s = rowptr_host[r], e = rowptr_host[r + 1];
+        if (e < s || e - s > INT32_MAX) return ADAQP_EINVAL;
+        for (int64_t j = s; j < e; ++j) {
+            const int32_t c = col_host[j];
+            if (c < 0 || c >= n_cols) return ADAQP_EINVAL;
+            if (j > s && col_host[j - 1] >= c) return ADAQP_EINVAL;        // rows must list ascending, distinct columns
+            ++uses[(size_t)c];
+        }
+    }
+    const int64_t total = e1 - e0;
+    col_bounds_out[0] = 0;
+    {
+        int64_t seen = 0;
+        int32_t c = 0;
+        for (int t = 1; t < kTiles; ++t) {
+            const int64_t want = (total * t + kTiles - 1) / kTiles;
+            while (c < n_cols && seen < want) seen += uses[(size_t)c++];
+            col_bounds_out[t] = c;
+        }
+        col_bounds_out[kTiles] = (int32_t)n_cols;
+    }
+    for (int64_t r = row_begin; r < row_end; ++r) {
+        const int32_t *cb = col_host + rowptr_host[r];
+        const int32_t *ce = col_host + rowptr_host[r + 1];
+        int32_t *off = tile_off_out + (r - row_begin) * (kTiles + 1);
+        for (int t = 0; t <= kTiles; ++t) off[t] = (int32_t)(std::lower_bound(cb, ce, col_bounds_out[t]) - cb);
+    }
+    return ADAQP_OK;
+}
+
+extern "C" int adaqp_spmm_tiled_workspace_bytes(int64_t n_rows, int32_t dim, int64_t *bytes_out)
+{
+    if (!bytes_out || n_rows < 0 || dim <= 0) return ADAQP_EINVAL;
+    if (n_rows > INT32_MAX - 1) return ADAQP_ESIZE;
+    *bytes_out = tiled_bytes(n_rows, dim);
+    return ADAQP_OK;
+}
+
+extern "C" int adaqp_spmm_csr_tiled(const int64_t *rowptr_dev, const int32_t *col_dev, const float *val_dev,
+                                    int64_t nnz, int64_t row_begin, int64_t row_end, const float *H_dev,
+                                    int64_t n_cols, int64_t ldh, int32_t dim, float *out_dev, int64_t ldo,
+                                    const int32_t *tile_off_dev, void *workspace_dev, int64_t workspace_bytes,
+                                    void *stream)
+{
+    if (row_begin < 0 || row_end < row_begin || nnz < 0 || dim <= 0 || ldh < dim || ldo < dim || n_cols < 0)
+        return ADAQP_EINVAL;
+    const int64_t n_rows = row_end - row_begin;
+    if (n_rows == 0) return ADAQP_OK;
+    if (!rowptr_dev || !out_dev || !tile_off_dev) return ADAQP_EINVAL;
+    if (nnz > 0 && (!col_dev || !val_dev || !H_dev || n_cols == 0)) return ADAQP_EINVAL;
+    if (n_rows > INT32_MAX - 1) return ADAQP_ESIZE;
+    if (!aligned_to(rowptr_dev, 8) || !aligned_to(col_dev, 4) || !aligned_to(val_dev, 4) ||
+        !aligned_to(tile_off_dev, 4))
+        return ADAQP_EINVAL;
+    // this kernel exists for the line-padded layout only: whole 128-byte lines in and out
+    if (ldh % 32 != 0 || ldo % 32 != 0 || !aligned_to(H_dev, 128) || !aligned_to(out_dev, 128)) return ADAQP_EINVAL;
+    const int64_t need = tiled_bytes(n_rows, dim);
+    if (!workspace_dev || !aligned_to(workspace_dev, 256)) return ADAQP_EINVAL;
+    if (workspace_bytes < need) return ADAQP_ESIZE;
+
+    TiledArgs a;
+    a.rowptr = rowptr_dev + row_begin;
+    a.col = col_dev;
+    a.val = val_dev;
+    a.nnz = nnz;
+    a.n_rows = (int32_t)n_rows;
+    a.tile_off = tile_off_dev;
+    a.H = H_dev;
+    a.n_cols = n_cols;
+    a.ldh = ldh;
+    a.dim = dim;
+    a.wdim = (dim + 31) / 32 * 32;
+    a.out = out_dev + row_begin * ldo;
+    a.ldo = ldo;
+    a.partial = reinterpret_cast<float *>(workspace_dev);
+    a.rows_per_wave = 4;
+    const int64_t rows_per_block = (int64_t)a.rows_per_wave * kWavesPerBlock;
+    a.n_row_blocks = (uint32_t)((n_rows + rows_per_block - 1) / rows_per_block);
+    // 128-column chunks halve the passes over the entries; 64-column chunks halve an XCD's working set
+    const bool wide = a.wdim >= 128;
+    const int cw = wide ? 128 : 64;
+    const int64_t n_chunks = (a.wdim + cw - 1) / cw;
+    const int64_t blocks = (int64_t)a.n_row_blocks * kTiles * n_chunks;
+    if (blocks > 0x7FFFFFFF) return ADAQP_ESIZE;
+    hipStream_t st = (hipStream_t)stream;
+    if (wide) hipLaunchKernelGGL((spmm_tiled_kernel<32, 8>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+    else hipLaunchKernelGGL((spmm_tiled_kernel<16, 8>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+    ADAQP_HIP_TRY(hipGetLastError());
+    const int64_t rblocks = (n_rows + kWavesPerBlock - 1) / kWavesPerBlock;
+    hipLaunchKernelGGL(spmm_tiled_reduce_kernel, dim3((unsigned)rblocks), dim3(kBlock), 0, st, a);
+    ADAQP_HIP_TRY(hipGetLastError());
+    return ADAQP_OK;
+}

@@ -87,8 +87,11 @@ def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
 
 
 class LayerStep:
+    TILED_MIN_MEAN_DEGREE = 128     # below this the per-(row, tile) partial sums cost more than the L2 re-use saves
+
     def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False,
-                 backward_receive: bool = True, trace: bool = True, fused_receive: bool = False):
+                 backward_receive: bool = True, trace: bool = True, fused_receive: bool = False,
+                 tiled: Optional[bool] = None):
         self.p = p
         self.device = torch.device(device)
         dev = self.device
@@ -128,10 +131,22 @@ class LayerStep:
         db, de = p.dependent_rows
         self.overlap_nnz = int(p.rowptr[oe] - p.rowptr[ob])
         self.dependent_nnz = int(p.rowptr[de] - p.rowptr[db])
-        self.ws_overlap = torch.empty(max(B.adaqp_spmm_workspace_bytes(oe - ob, self.overlap_nnz, cfg.dim), 256),
-                                      dtype=torch.uint8, device=dev)
-        self.ws_dependent = torch.empty(max(B.adaqp_spmm_workspace_bytes(de - db, self.dependent_nnz, cfg.dim), 256),
-                                        dtype=torch.uint8, device=dev)
+        # aggregation tiled over the L2 caches: pays when rows are long (every row of feat re-used many times).
+        # tiled=None decides per row range from the mean row length.
+        self.tile_off_overlap = self.tile_off_dependent = None
+        ws_o = B.adaqp_spmm_workspace_bytes(oe - ob, self.overlap_nnz, cfg.dim)
+        ws_d = B.adaqp_spmm_workspace_bytes(de - db, self.dependent_nnz, cfg.dim)
+        if pad and tiled is not False:
+            if oe > ob and (tiled or self.overlap_nnz >= self.TILED_MIN_MEAN_DEGREE * (oe - ob)):
+                _, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, ob, oe, p.feat.shape[0])
+                self.tile_off_overlap = torch.from_numpy(off).to(dev)
+                ws_o = max(ws_o, B.adaqp_spmm_tiled_workspace_bytes(oe - ob, cfg.dim))
+            if de > db and (tiled or self.dependent_nnz >= self.TILED_MIN_MEAN_DEGREE * (de - db)):
+                _, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, db, de, p.feat.shape[0])
+                self.tile_off_dependent = torch.from_numpy(off).to(dev)
+                ws_d = max(ws_d, B.adaqp_spmm_tiled_workspace_bytes(de - db, cfg.dim))
+        self.ws_overlap = torch.empty(max(ws_o, 256), dtype=torch.uint8, device=dev)
+        self.ws_dependent = torch.empty(max(ws_d, 256), dtype=torch.uint8, device=dev)
         self.stream_msg = torch.cuda.Stream(device=dev)
         self.stream_agg = torch.cuda.Stream(device=dev)
         self.event_fork = HipEvent()
@@ -163,6 +178,9 @@ class LayerStep:
         d.recv_order_dev = pl.recv_order.data_ptr() if (self.use_recv_order and pl.recv_order is not None
                                                         and not self.backward) else None
         d.slot_of_row_dev = self.slot_of_row.data_ptr() if self.fused_receive else None
+        d.tile_off_overlap_dev = None if self.tile_off_overlap is None else self.tile_off_overlap.data_ptr()
+        d.tile_off_dependent_dev = None if (self.tile_off_dependent is None or self.fused_receive) \
+            else self.tile_off_dependent.data_ptr()
         if self.backward and self.backward_receive and pl.seg_order is not None:
             d.recv_seg_order_dev, d.recv_seg_ptr_dev = pl.seg_order.data_ptr(), pl.seg_ptr.data_ptr()
             d.n_recv_seg = pl.seg_ptr.shape[0] - 1

@@ -442,6 +442,75 @@ def test_spmm_packed_argument_checks():
 
 
 # ------------------------------------------------------------------------------------------------------
+# aggregation tiled over the L2 caches (long rows)
+# ------------------------------------------------------------------------------------------------------
+
+def _gpu_spmm_tiled(rowptr, col, val, rb, re, H, dim, ldo):
+    n_cols = H.shape[0]
+    bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, rb, re, n_cols)
+    out = torch.full((rowptr.shape[0] - 1, ldo), 7.0, dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(B.adaqp_spmm_tiled_workspace_bytes(re - rb, dim), 256), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)                                              # NaN patterns: unread unless written first
+    B.adaqp_spmm_csr_tiled(torch.from_numpy(rowptr).to(DEV), torch.from_numpy(col).to(DEV),
+                           torch.from_numpy(val).to(DEV), rb, re, torch.from_numpy(H).to(DEV), dim, out,
+                           torch.from_numpy(off).to(DEV), ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), bounds, off
+
+
+@pytest.mark.parametrize("dim,ld", [(128, 128), (602, 608), (64, 64), (7, 32), (60, 64), (96, 96), (100, 128),
+                                    (130, 160), (256, 256), (2049, 2080)])
+def test_spmm_tiled(oracle, dim, ld):
+    _say(f"tiled spmm dim={dim} ld={ld}")
+    rng = np.random.default_rng(2000 + dim)
+    n_rows, n_cols = 300, 900
+    degs = rng.integers(0, 150, size=n_rows)
+    degs[10] = 880                                                     # nearly every column
+    degs[11] = 0
+    degs[100:110] = 0
+    degs[200:230] = rng.integers(1, 4, size=30)                        # rows that miss most tiles
+    rowptr, col, val = _random_graph(rng, n_rows, n_cols, degs)
+    H = np.full((n_cols, ld), np.nan, dtype=np.float32)                # NaN in the row padding
+    H[:, :dim] = rng.standard_normal((n_cols, dim), dtype=np.float32)
+    got, bounds, off = _gpu_spmm_tiled(rowptr, col, val, 0, n_rows, H, dim, ld)
+    # the plan: tiles cover the columns, hold about an eighth of the entries each, and count each row's entries
+    assert bounds[0] == 0 and bounds[-1] == n_cols and np.all(np.diff(bounds) >= 0)
+    per_tile = np.histogram(col, bins=bounds.astype(np.int64))[0] if False else \
+        np.array([np.count_nonzero((col >= bounds[t]) & (col < bounds[t + 1])) for t in range(B.SPMM_TILES)])
+    assert per_tile.sum() == len(col) and per_tile.max() <= len(col) / B.SPMM_TILES + degs.max()
+    for r in (0, 10, 11, 205, 299):
+        c = col[rowptr[r]: rowptr[r + 1]]
+        assert [int(np.count_nonzero(c < b)) for b in bounds] == off[r].tolist()
+    want, mag = oracle.spmm_csr(rowptr, col, val, 0, n_rows, np.ascontiguousarray(H[:, :dim]), dim)
+    err = np.abs(got[:, :dim].astype(np.float64) - want)
+    worst = float((err / (SPMM_RTOL * mag + 1e-30)).max())
+    assert worst <= 1.0, f"worst error {worst:.3f} x tolerance"
+    zero_to = _padded_cols(dim, ld)
+    assert np.all(got[:, dim:zero_to] == 0.0) and np.all(got[:, zero_to:] == 7.0)
+    again, _, _ = _gpu_spmm_tiled(rowptr, col, val, 0, n_rows, H, dim, ld)
+    assert np.array_equal(got.view(np.uint32), again.view(np.uint32)), "runs differ"
+    sub, _, _ = _gpu_spmm_tiled(rowptr, col, val, 9, 120, H, dim, ld)
+    assert np.all(sub[:9] == 7.0) and np.all(sub[120:] == 7.0)
+    err = np.abs(sub[9:120, :dim].astype(np.float64) - want[9:120])
+    assert np.all(err <= SPMM_RTOL * mag[9:120] + 1e-30)
+
+
+def test_spmm_tiled_rejects_what_it_cannot_do():
+    rowptr = np.array([0, 2], dtype=np.int64)
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_plan_spmm_tiles(rowptr, np.array([3, 1], dtype=np.int32), 0, 1, 8)        # not ascending
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_plan_spmm_tiles(rowptr, np.array([1, 9], dtype=np.int32), 0, 1, 8)        # out of range
+    _, off = B.adaqp_plan_spmm_tiles(rowptr, np.array([1, 3], dtype=np.int32), 0, 1, 8)
+    H = torch.zeros((8, 30), dtype=torch.float32, device=DEV)                              # pitch not whole lines
+    out = torch.zeros((1, 30), dtype=torch.float32, device=DEV)
+    ws = torch.empty(4096, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_spmm_csr_tiled(torch.from_numpy(rowptr).to(DEV), torch.tensor([1, 3], dtype=torch.int32, device=DEV),
+                               torch.ones(2, device=DEV), 0, 1, H, 30, out, torch.from_numpy(off).to(DEV), ws)
+
+
+# ------------------------------------------------------------------------------------------------------
 # the layer step
 # ------------------------------------------------------------------------------------------------------
 
@@ -603,3 +672,33 @@ def test_trace_assign_replan_loop(oracle):
     assert np.array_equal(L2.recv_packed.cpu().numpy()[: L2.plan.packed_bytes], packed_w)
     assert np.array_equal(L2.feat.cpu().numpy().view(np.uint32), feat_w.view(np.uint32))
     assert np.all(np.abs(L2.out.cpu().numpy().astype(np.float64) - out64) <= SPMM_RTOL * mag + 1e-30)
+
+
+@pytest.mark.parametrize("name", ["c0", "c0_backward"])
+def test_layer_step_with_tiled_aggregation(oracle, name):
+    """Both row ranges through the L2-tiled kernel, every schedule, forward and backward."""
+    if name == "c0":
+        p = make_partition(CONFIGS["c0"])
+    else:
+        p = make_partition(replace(CONFIGS["c4"], n_local=2000, n_halo=1800, n_send=1500, mean_degree=9.0, dim=128))
+    cfg = p.cfg
+    seed = 4321
+    packed_w, params_w, feat_w, out64, mag = _oracle_layer(oracle, p, seed)
+    first = None
+    for schedule in (B.SERIAL, B.ISOLATED, B.FREE):
+        L = LayerStep(p, DEV, seed=seed, tiled=True, backward_receive=False)
+        assert L.tile_off_overlap is not None and L.tile_off_dependent is not None
+        if not cfg.backward:
+            L.feat[cfg.n_local: cfg.n_local + cfg.n_send] = float("nan")
+        L.out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        L.run(schedule)
+        L.synchronize()
+        out = L.out.cpu().numpy()
+        assert np.all(np.abs(out.astype(np.float64) - out64) <= SPMM_RTOL * mag + 1e-30), f"schedule {schedule}"
+        if not cfg.backward:
+            assert np.array_equal(L.recv_packed.cpu().numpy()[: L.plan.packed_bytes], packed_w)
+            assert np.array_equal(L.feat.cpu().numpy().view(np.uint32), feat_w.view(np.uint32))
+        if first is None:
+            first = out
+        assert np.array_equal(out.view(np.uint32), first.view(np.uint32)), "schedules disagree"
