@@ -249,9 +249,9 @@ int adaqp_plan_spmm_tiles(const int64_t *rowptr_host, const int32_t *col_host, i
 int adaqp_spmm_tiled_workspace_bytes(int64_t n_rows, int32_t dim, int64_t *bytes_out);
 
 /* out[r, 0:dim] = sum_j val[j] * H[col[j], 0:dim] for r in [row_begin, row_end), like adaqp_spmm_csr.
- * tile_off_dev: device copy of adaqp_plan_spmm_tiles' table for the same row range.  Entries whose column is
- * out of range are skipped; a table that disagrees with rowptr is clamped to the row (wrong sums, no stray
- * access).  The summation order is fixed by the table and the launch geometry: runs are bit-identical.
+ * tile_off_dev: device copy of adaqp_plan_spmm_tiles' table for the same row range (planning rejects graphs
+ * with out-of-range columns; should the device arrays hold one nevertheless, it is read as column 0 with
+ * coefficient 0).  A table that disagrees with rowptr is clamped to the row (wrong sums, no stray access).  The summation order is fixed by the table and the launch geometry: runs are bit-identical.
  * H and out must be line-padded (pitch a multiple of 32 floats, base 128-byte aligned); the padding of the
  * written rows is set to zero.  workspace_dev: 256-byte aligned, >= adaqp_spmm_tiled_workspace_bytes.
  * Errors: EINVAL (layout, alignment, null), ESIZE (workspace too small, too many rows), EHIP. */

@@ -13,6 +13,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <type_traits>
 #include <vector>
 
 #include "adaqp.h"
@@ -84,14 +85,21 @@ __device__ __forceinline__ float shuffle_f32(float v, int src_lane)
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src_lane << 2, __builtin_bit_cast(int32_t, v)));
 }
 
-// LPE lanes share one entry (each lane four columns): 16 -> chunks of 64 columns, 32 -> chunks of 128.
-// A wave has 64 / LPE entries in each load instruction and U such loads in flight.
-template <int LPE, int U>
+// LPE lanes share one entry; each lane holds VPL vectors of four columns, LPE * 4 columns apart, so a chunk is
+// CW = LPE * 4 * VPL columns and every load instruction reads whole 128-byte lines.  One "step" fetches
+// SLOTS = 64 / LPE entries with VPL loads that share the column lookup and the address arithmetic; up to
+// 8 / VPL steps (8 KB per wave) are in flight, and the tail of a segment is issued in groups of 4, 2 and 1 steps
+// so that a row with two entries in this tile costs one load, not eight.  The inner loop is branch-free: per
+// step two cross-lane reads (column, coefficient), one 32 x 32 -> 64-bit multiply-add for the address, VPL loads,
+// 4 * VPL multiply-adds.  Measured on this part the kernel is bound by the rate at which a CU's vector memory
+// pipeline takes 16-byte-per-lane gathers (about 22 TB/s over the chip with every row L1-resident), not by L2.
+template <int LPE, int VPL>
 __global__ __launch_bounds__(kBlock) void spmm_tiled_kernel(const TiledArgs a)
 {
     constexpr int SLOTS = kWave / LPE;
-    constexpr int CW = LPE * 4;
-    static_assert(LPE % U == 0, "a batch of 64 entries is LPE load steps: a whole number of U-step groups");
+    constexpr int CW = LPE * 4 * VPL;
+    constexpr int UMAX = 8 / VPL;                           // load steps in flight: 8 KB per wave
+    static_assert(LPE % UMAX == 0, "a batch of 64 entries is LPE load steps: a whole number of full groups");
     const int lane = threadIdx.x & (kWave - 1);
     const int q = lane / LPE, l = lane % LPE;
     // the tile is the fastest-running index: consecutive workgroups land on consecutive XCDs
@@ -99,64 +107,146 @@ __global__ __launch_bounds__(kBlock) void spmm_tiled_kernel(const TiledArgs a)
     const uint32_t rest = blockIdx.x / kTiles;
     const uint32_t rb = rest % a.n_row_blocks;
     const uint32_t chunk = rest / a.n_row_blocks;
-    const int32_t c0 = (int32_t)chunk * CW + l * 4;
-    const bool live = c0 < a.wdim;                          // wdim is a multiple of 32: a live vector is whole
-    const int wave = threadIdx.x >> 6;
+    const int32_t c0 = (int32_t)chunk * CW + l * 4;         // first vector of the lane; vector v is LPE * 4 columns on
+    bool live[VPL];                                         // wdim is a multiple of 32: a live vector is whole
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) live[v] = c0 + v * LPE * 4 < a.wdim;
+    const int wave = uniform_i32((int32_t)(threadIdx.x >> 6));
     const int64_t r_begin = ((int64_t)rb * kWavesPerBlock + wave) * a.rows_per_wave;
-    const int64_t r_end = r_begin + a.rows_per_wave < a.n_rows ? r_begin + a.rows_per_wave : a.n_rows;
-    const float *hbase = a.H + (live ? c0 : 0);
+    if (r_begin >= a.n_rows) return;
+    const int32_t n_mine = (int32_t)(r_begin + a.rows_per_wave < a.n_rows ? a.rows_per_wave : a.n_rows - r_begin);
+    // a vector past the row's end is read from the start of the row instead and never stored: no masked loads
+    const float *hlane[VPL];
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) hlane[v] = a.H + (live[v] ? c0 + v * LPE * 4 : 0);
+    const uint32_t pitch = (uint32_t)a.ldh * 4u;            // bytes; the host checks that it fits
 
-    for (int64_t r = r_begin; r < r_end; ++r) {
-        int64_t first;
-        int32_t count;
-        segment(a, r, (int)tile, &first, &count);
-        first = (int64_t)(((uint64_t)(uint32_t)uniform_i32((int32_t)(first >> 32)) << 32) |
-                          (uint32_t)uniform_i32((int32_t)first));
-        count = uniform_i32(count);
-        if (count == 0) continue;                           // the reduction skips this partial as well
-        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int32_t j = 0; j < count; j += kWave) {
-            const int32_t nb = count - j < kWave ? count - j : kWave;
-            // lane i holds entry j + i.  A lane without an entry, or with an out-of-range column, holds the
-            // complement of a column that is safe to read (negative): the row is fetched and then dropped
-            const int32_t mine = lane < nb ? lane : 0;
-            int32_t my_col = __builtin_nontemporal_load(a.col + first + j + mine);
-            const float my_val = __builtin_nontemporal_load(a.val + first + j + mine);
-            if (my_col < 0 || my_col >= a.n_cols) my_col = ~0;
-            else if (lane >= nb) my_col = ~my_col;
-            const int32_t n_it = (nb + SLOTS - 1) / SLOTS;
-            for (int32_t it = 0; it < n_it; it += U) {
-                float h[U][4];
-                float alpha[U];
+    // lanes 0..n_mine-1 look up their row's segment (one memory round trip for all the wave's rows)
+    int64_t my_first = 0;
+    int32_t my_count = 0;
+    if (lane < n_mine) segment(a, r_begin + lane, (int)tile, &my_first, &my_count);
+    const int32_t my_first_lo = (int32_t)(uint32_t)my_first, my_first_hi = (int32_t)(my_first >> 32);
+    uint64_t todo = __ballot(my_count > 0);                 // rows that have entries in this tile
+    if (todo == 0) return;                                  // the reduction skips these partials as well
+
+    // the wave's work as a sequence of batches of up to 64 entries of one row; the next batch's (col, val) are
+    // requested before the current batch is worked on
+    int32_t row = (int32_t)__builtin_ctzll(todo);           // relative to r_begin
+    int64_t first = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane(my_first_hi, row) << 32) |
+                              (uint32_t)__builtin_amdgcn_readlane(my_first_lo, row));
+    int32_t count = __builtin_amdgcn_readlane(my_count, row);
+    int32_t j = 0;
+    auto request = [&](int32_t *col_out, float *val_out) {
+        // lane i holds entry j + i.  A lane without an entry repeats the batch's first entry with a zero
+        // coefficient (a row that is being fetched anyway); an out-of-range column reads row 0 likewise
+        const int32_t nb = count - j < kWave ? count - j : kWave;
+        const int32_t mine = lane < nb ? lane : 0;
+        *col_out = __builtin_nontemporal_load(a.col + first + j + mine);
+        *val_out = __builtin_nontemporal_load(a.val + first + j + mine);
+    };
+    int32_t nx_col;
+    float nx_val;
+    request(&nx_col, &nx_val);
+
+    float acc[VPL][4];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    // (it + u) * SLOTS + q <= 63: n_it <= 64 / SLOTS, which is a multiple of U
-                    const int e = ((it + u) * SLOTS + q) & (kWave - 1);
-                    const int32_t c = shuffle_i32(my_col, e);
-                    alpha[u] = shuffle_f32(my_val, e);
-                    const bool use = c >= 0 && live;
-                    const int32_t row = c ^ (c >> 31);                  // c if c >= 0, else ~c
-                    float4 x = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                    if (use) x = *reinterpret_cast<const float4 *>(hbase + (int64_t)row * a.ldh);   // masked lanes: no traffic
-                    h[u][0] = x.x;
-                    h[u][1] = x.y;
-                    h[u][2] = x.z;
-                    h[u][3] = x.w;
-                }
+    for (int v = 0; v < VPL; ++v)
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) acc[k] = fmaf(alpha[u], h[u][k], acc[k]);
+        for (int k = 0; k < 4; ++k) acc[v][k] = 0.0f;
+
+    for (;;) {
+        const int32_t nb = count - j < kWave ? count - j : kWave;
+        const int32_t this_row = row;
+        const bool row_ends = j + kWave >= count;
+        int32_t my_col = nx_col;
+        float my_val = nx_val;
+        if (lane >= nb) my_val = 0.0f;
+        if ((uint32_t)my_col >= (uint32_t)a.n_cols) { my_col = 0; my_val = 0.0f; }
+        // move on and request the next batch
+        bool more = true;
+        if (!row_ends) {
+            j += kWave;
+        } else {
+            todo &= todo - 1;
+            if (todo != 0) {
+                row = (int32_t)__builtin_ctzll(todo);
+                first = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane(my_first_hi, row) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readlane(my_first_lo, row));
+                count = __builtin_amdgcn_readlane(my_count, row);
+                j = 0;
+            } else {
+                more = false;
             }
         }
-        // the SLOTS partial sums of the row, combined pairwise in a fixed order
+        if (more) request(&nx_col, &nx_val);
+
+        const int32_t n_it = (nb + SLOTS - 1) / SLOTS;
+        // UU load steps at once, starting at step `it`
+        auto group = [&](auto uu_tag, int32_t it) {
+            constexpr int UU = decltype(uu_tag)::value;
+            float h[UU][VPL][4];
+            float alpha[UU];
 #pragma unroll
-        for (int step = LPE; step < kWave; step <<= 1)
+            for (int u = 0; u < UU; ++u) {
+                const int e = ((it + u) * SLOTS + q) & (kWave - 1);            // < 64: it + u < LPE
+                const uint32_t c = (uint32_t)shuffle_i32(my_col, e);
+                alpha[u] = shuffle_f32(my_val, e);
+                const uint64_t off = (uint64_t)c * pitch;                      // one 32 x 32 -> 64 multiply
 #pragma unroll
-            for (int k = 0; k < 4; ++k) acc[k] += shuffle_f32(acc[k], lane ^ step);
-        if (q == 0 && live) {
-            store4_streaming(a.partial + ((int64_t)tile * a.n_rows + r) * a.wdim + c0, acc);
+                for (int v = 0; v < VPL; ++v) {
+                    const float4 x = *reinterpret_cast<const float4 *>(
+                        reinterpret_cast<const char *>(hlane[v]) + off);
+                    h[u][v][0] = x.x;
+                    h[u][v][1] = x.y;
+                    h[u][v][2] = x.z;
+                    h[u][v][3] = x.w;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UU; ++u)
+#pragma unroll
+                for (int v = 0; v < VPL; ++v)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) acc[v][k] = fmaf(alpha[u], h[u][v][k], acc[v][k]);
+        };
+        int32_t it = 0;
+        for (; it + UMAX <= n_it; it += UMAX) group(std::integral_constant<int, UMAX>(), it);
+        if constexpr (UMAX >= 8) {
+            if (it + 4 <= n_it) {
+                group(std::integral_constant<int, 4>(), it);
+                it += 4;
+            }
         }
+        if constexpr (UMAX >= 4) {
+            if (it + 2 <= n_it) {
+                group(std::integral_constant<int, 2>(), it);
+                it += 2;
+            }
+        }
+        if constexpr (UMAX >= 2) {
+            if (it < n_it) group(std::integral_constant<int, 1>(), it);
+        }
+
+        if (row_ends) {
+            // the SLOTS partial sums of the row, combined pairwise in a fixed order
+#pragma unroll
+            for (int step = LPE; step < kWave; step <<= 1)
+#pragma unroll
+                for (int v = 0; v < VPL; ++v)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) acc[v][k] += shuffle_f32(acc[v][k], lane ^ step);
+            if (q == 0) {
+                float *p = a.partial + ((int64_t)tile * a.n_rows + r_begin + this_row) * a.wdim + c0;
+#pragma unroll
+                for (int v = 0; v < VPL; ++v)
+                    if (live[v]) store4_streaming(p + v * LPE * 4, acc[v]);
+            }
+#pragma unroll
+            for (int v = 0; v < VPL; ++v)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc[v][k] = 0.0f;
+        }
+        if (!more) break;
     }
 }
 
@@ -279,6 +369,7 @@ extern "C" int adaqp_spmm_csr_tiled(const int64_t *rowptr_dev, const int32_t *co
         return ADAQP_EINVAL;
     // this kernel exists for the line-padded layout only: whole 128-byte lines in and out
     if (ldh % 32 != 0 || ldo % 32 != 0 || !aligned_to(H_dev, 128) || !aligned_to(out_dev, 128)) return ADAQP_EINVAL;
+    if (ldh >= ((int64_t)1 << 30)) return ADAQP_ESIZE;                          // the row pitch in bytes stays in 32 bits
     const int64_t need = tiled_bytes(n_rows, dim);
     if (!workspace_dev || !aligned_to(workspace_dev, 256)) return ADAQP_EINVAL;
     if (workspace_bytes < need) return ADAQP_ESIZE;
@@ -298,18 +389,19 @@ extern "C" int adaqp_spmm_csr_tiled(const int64_t *rowptr_dev, const int32_t *co
     a.out = out_dev + row_begin * ldo;
     a.ldo = ldo;
     a.partial = reinterpret_cast<float *>(workspace_dev);
-    a.rows_per_wave = 4;
+    a.rows_per_wave = 4;                                    // <= 64: a wave keeps its rows' segments in lanes
     const int64_t rows_per_block = (int64_t)a.rows_per_wave * kWavesPerBlock;
     a.n_row_blocks = (uint32_t)((n_rows + rows_per_block - 1) / rows_per_block);
-    // 128-column chunks halve the passes over the entries; 64-column chunks halve an XCD's working set
+    // 128-column chunks (32 lanes x one vector per entry) where the rows are at least that wide; narrower
+    // matrices take 64-column chunks so that no lane idles
     const bool wide = a.wdim >= 128;
     const int cw = wide ? 128 : 64;
     const int64_t n_chunks = (a.wdim + cw - 1) / cw;
     const int64_t blocks = (int64_t)a.n_row_blocks * kTiles * n_chunks;
     if (blocks > 0x7FFFFFFF) return ADAQP_ESIZE;
     hipStream_t st = (hipStream_t)stream;
-    if (wide) hipLaunchKernelGGL((spmm_tiled_kernel<32, 8>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
-    else hipLaunchKernelGGL((spmm_tiled_kernel<16, 8>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+    if (wide) hipLaunchKernelGGL((spmm_tiled_kernel<32, 1>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+    else hipLaunchKernelGGL((spmm_tiled_kernel<16, 1>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
     ADAQP_HIP_TRY(hipGetLastError());
     const int64_t rblocks = (n_rows + kWavesPerBlock - 1) / kWavesPerBlock;
     hipLaunchKernelGGL(spmm_tiled_reduce_kernel, dim3((unsigned)rblocks), dim3(kBlock), 0, st, a);
