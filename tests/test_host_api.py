@@ -133,3 +133,36 @@ def test_plan_slot_of_row():
         B.adaqp_plan_slot_of_row(10, np.array([1, 1], dtype=np.int32))       # a row listed twice
     with pytest.raises(B.AdaqpError):
         B.adaqp_plan_slot_of_row(10, np.array([10], dtype=np.int32))         # out of range
+
+
+def test_plan_spmm_tiles():
+    rng = np.random.default_rng(3)
+    n_rows, n_cols = 40, 100
+    rowptr = np.zeros(n_rows + 1, dtype=np.int64)
+    cols = []
+    for r in range(n_rows):
+        d = int(rng.integers(0, 30))
+        cols.append(np.sort(rng.choice(n_cols, size=d, replace=False)))
+        rowptr[r + 1] = rowptr[r] + d
+    col = np.concatenate(cols).astype(np.int32)
+    bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, 0, n_rows, n_cols)
+    assert bounds.shape == (B.SPMM_TILES + 1,) and off.shape == (n_rows, B.SPMM_TILES + 1)
+    assert bounds[0] == 0 and bounds[-1] == n_cols and np.all(np.diff(bounds) >= 0)
+    for r in range(n_rows):
+        c = col[rowptr[r]: rowptr[r + 1]]
+        assert off[r].tolist() == [int(np.count_nonzero(c < b)) for b in bounds]
+    per_tile = np.array([np.count_nonzero((col >= bounds[t]) & (col < bounds[t + 1])) for t in range(B.SPMM_TILES)])
+    uses = np.bincount(col, minlength=n_cols)
+    assert per_tile.sum() == len(col)
+    assert np.all(np.abs(per_tile - len(col) / B.SPMM_TILES) <= uses.max() + 1)      # equal up to one column's uses
+    # a sub-range is planned from its own entries and indexed from its first row
+    b2, off2 = B.adaqp_plan_spmm_tiles(rowptr, col, 10, 25, n_cols)
+    assert off2.shape == (15, B.SPMM_TILES + 1)
+    c = col[rowptr[12]: rowptr[13]]
+    assert off2[2].tolist() == [int(np.count_nonzero(c < b)) for b in b2]
+    # empty range, empty graph
+    b3, off3 = B.adaqp_plan_spmm_tiles(rowptr, col, 5, 5, n_cols)
+    assert off3.shape == (0, B.SPMM_TILES + 1) and b3[-1] == n_cols
+    assert B.adaqp_spmm_tiled_workspace_bytes(10, 602) == 8 * 10 * 608 * 4
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_plan_spmm_tiles(np.array([0, 2], np.int64), np.array([5, 5], np.int32), 0, 1, 8)   # repeated column
