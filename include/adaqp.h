@@ -237,11 +237,14 @@ int adaqp_spmm_csr_packed(const int64_t *rowptr_dev, const int32_t *col_dev, con
  * caches keeps re-using one range of the rows of H.  The graph's columns are cut into ADAQP_SPMM_TILES ranges
  * with equal entry counts, once per graph, on the host.  Line-padded layout only. */
 #define ADAQP_SPMM_TILES 8
+#define ADAQP_SPMM_TILED_SHORT_ROW 64   /* rows with fewer entries are kept whole in one tile */
 
 /* Host only.  For rows [row_begin, row_end) of a host CSR whose rows list ascending, distinct, in-range
  * columns: col_bounds_out[ADAQP_SPMM_TILES + 1] (0 = bounds[0] <= ... <= bounds[TILES] = n_cols) and
- * tile_off_out[(row_end - row_begin) * (ADAQP_SPMM_TILES + 1)]: entry t of a row = number of its entries with
- * column < bounds[t].  Errors: EINVAL (unsorted / repeated / out-of-range column, bad rowptr). */
+ * tile_off_out[(row_end - row_begin) * (ADAQP_SPMM_TILES + 1)]: entry t of a row = number of its entries that
+ * belong to tiles before t.  For a row of at least ADAQP_SPMM_TILED_SHORT_ROW entries that is the number of
+ * entries with column < bounds[t]; a shorter row is assigned whole to tile (row - row_begin) mod
+ * ADAQP_SPMM_TILES (eight segments of one or two entries each would cost more than they save).  Errors: EINVAL (unsorted / repeated / out-of-range column, bad rowptr). */
 int adaqp_plan_spmm_tiles(const int64_t *rowptr_host, const int32_t *col_host, int64_t row_begin, int64_t row_end,
                           int64_t n_cols, int32_t *col_bounds_out, int32_t *tile_off_out);
 

@@ -254,6 +254,7 @@ def adaqp_spmm_csr(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, r
 
 
 SPMM_TILES = 8
+SPMM_TILED_SHORT_ROW = 64
 
 
 def adaqp_plan_spmm_tiles(rowptr_host: np.ndarray, col_host: np.ndarray, row_begin: int, row_end: int,

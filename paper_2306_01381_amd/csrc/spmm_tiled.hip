@@ -338,7 +338,15 @@ extern "C" int adaqp_plan_spmm_tiles(const int64_t *rowptr_host, const int32_t *
         const int32_t *cb = col_host + rowptr_host[r];
         const int32_t *ce = col_host + rowptr_host[r + 1];
         int32_t *off = tile_off_out + (r - row_begin) * (kTiles + 1);
-        for (int t = 0; t <= kTiles; ++t) off[t] = (int32_t)(std::lower_bound(cb, ce, col_bounds_out[t]) - cb);
+        const int32_t degree = (int32_t)(ce - cb);
+        if (degree < ADAQP_SPMM_TILED_SHORT_ROW) {
+            // a short row is not worth eight segments: all of it goes to one tile (rows take turns), its few
+            // neighbour rows outside that tile's column range are fetched past the L2
+            const int home = (int)((r - row_begin) % kTiles);
+            for (int t = 0; t <= kTiles; ++t) off[t] = t <= home ? 0 : degree;
+        } else {
+            for (int t = 0; t <= kTiles; ++t) off[t] = (int32_t)(std::lower_bound(cb, ce, col_bounds_out[t]) - cb);
+        }
     }
     return ADAQP_OK;
 }

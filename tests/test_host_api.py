@@ -141,16 +141,21 @@ def test_plan_spmm_tiles():
     rowptr = np.zeros(n_rows + 1, dtype=np.int64)
     cols = []
     for r in range(n_rows):
-        d = int(rng.integers(0, 30))
+        d = int(rng.integers(0, 30)) if r % 3 else int(rng.integers(64, 100))      # short and long rows
         cols.append(np.sort(rng.choice(n_cols, size=d, replace=False)))
         rowptr[r + 1] = rowptr[r] + d
     col = np.concatenate(cols).astype(np.int32)
     bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, 0, n_rows, n_cols)
     assert bounds.shape == (B.SPMM_TILES + 1,) and off.shape == (n_rows, B.SPMM_TILES + 1)
     assert bounds[0] == 0 and bounds[-1] == n_cols and np.all(np.diff(bounds) >= 0)
+    def want_row(r, first_row, c, bnd):
+        if len(c) >= B.SPMM_TILED_SHORT_ROW:
+            return [int(np.count_nonzero(c < b)) for b in bnd]
+        home = (r - first_row) % B.SPMM_TILES                      # a short row stays whole, in one tile
+        return [0 if t <= home else len(c) for t in range(B.SPMM_TILES + 1)]
+
     for r in range(n_rows):
-        c = col[rowptr[r]: rowptr[r + 1]]
-        assert off[r].tolist() == [int(np.count_nonzero(c < b)) for b in bounds]
+        assert off[r].tolist() == want_row(r, 0, col[rowptr[r]: rowptr[r + 1]], bounds)
     per_tile = np.array([np.count_nonzero((col >= bounds[t]) & (col < bounds[t + 1])) for t in range(B.SPMM_TILES)])
     uses = np.bincount(col, minlength=n_cols)
     assert per_tile.sum() == len(col)
@@ -158,8 +163,8 @@ def test_plan_spmm_tiles():
     # a sub-range is planned from its own entries and indexed from its first row
     b2, off2 = B.adaqp_plan_spmm_tiles(rowptr, col, 10, 25, n_cols)
     assert off2.shape == (15, B.SPMM_TILES + 1)
-    c = col[rowptr[12]: rowptr[13]]
-    assert off2[2].tolist() == [int(np.count_nonzero(c < b)) for b in b2]
+    for r in (12, 13, 14, 15):
+        assert off2[r - 10].tolist() == want_row(r, 10, col[rowptr[r]: rowptr[r + 1]], b2)
     # empty range, empty graph
     b3, off3 = B.adaqp_plan_spmm_tiles(rowptr, col, 5, 5, n_cols)
     assert off3.shape == (0, B.SPMM_TILES + 1) and b3[-1] == n_cols
