@@ -8,7 +8,8 @@ the timed region starts.
 
 Prints ONE JSON line.  `value` is whole-step throughput in aggregated edges per second; the codec kernels'
 GB/s and every kernel's fraction of the 8 TB/s HBM peak are in `kernels`; `roofline` describes the dominant
-kernel (the merge-path SpMM); `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+kernel (the SpMM: tiled over the L2 caches where the rows are long, merge-path otherwise); `cpu_baseline` is the
+CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
