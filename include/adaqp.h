@@ -315,7 +315,10 @@ typedef struct adaqp_layer_desc {
                                                layout required; the range's workspace must then hold
                                                adaqp_spmm_tiled_workspace_bytes as well).  With a table for the
                                                dependent range, slot_of_row_dev is ignored: the received rows are
-                                               de-quantised into feat */
+                                               de-quantised into feat.  With tables for both ranges the dependent
+                                               aggregation waits for the other one in every schedule (two tiled
+                                               launches at once would share each L2 between two column ranges);
+                                               the overlap with the message path stays */
     const int32_t *recv_seg_order_dev;  /* backward only, optional: adaqp_plan_recv_segments of halo_idx */
     const int64_t *recv_seg_ptr_dev;
     int64_t n_recv_seg;

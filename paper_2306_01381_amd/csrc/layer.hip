@@ -223,6 +223,10 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
         int64_t need = 0;
         rc = adaqp_spmm_workspace_bytes(rows, nz, d->dim, &need);
         if (rc != ADAQP_OK) return rc;
+        if (part ? d->tile_off_overlap_dev != nullptr : d->tile_off_dependent_dev != nullptr) {
+            rc = adaqp_spmm_tiled_workspace_bytes(rows, d->dim, &need);         // that range takes the tiled kernel
+            if (rc != ADAQP_OK) return rc;
+        }
         const int64_t have = part ? d->workspace_overlap_bytes : d->workspace_dependent_bytes;
         const void *ws = part ? d->workspace_overlap_dev : d->workspace_dependent_dev;
         if (rows > 0 && need > 0 && (!ws || have < need)) return ADAQP_ESIZE;
@@ -232,6 +236,7 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
     hipStream_t agg = d->schedule == ADAQP_SERIAL ? msg : (hipStream_t)d->stream_agg;
     hipEvent_t fork = (hipEvent_t)d->event_fork, join = (hipEvent_t)d->event_join;
     const bool forward = d->direction == ADAQP_FORWARD;
+    const bool both_tiled = d->tile_off_overlap_dev && d->tile_off_dependent_dev;
     bool forked = false;
     auto fork_now = [&]() -> int {
         if (d->schedule == ADAQP_SERIAL) return ADAQP_OK;
@@ -272,6 +277,9 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
                                             d->row_offset_dev, d->halo_idx_dev, d->recv_order_dev, d->n_send, d->dim,
                                             d->feat_dev, d->n_feat_rows, d->ld, msg));
         if (d->schedule == ADAQP_SERIAL) ADAQP_STEP(aggregate(d, true, msg));
+        // two tiled aggregations side by side would bring two column ranges to every L2 and lose what the
+        // tiling is for: the dependent one waits for the other (which has overlapped the message path by now)
+        if (both_tiled) ADAQP_STEP(join_now());
         ADAQP_STEP(aggregate(d, false, msg));
     } else {
         // backward: the rows that are sent are aggregated first, the local rows overlap their quantisation
@@ -279,6 +287,7 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
         if (d->schedule == ADAQP_FREE) {
             ADAQP_STEP(fork_now());
             ADAQP_STEP(aggregate(d, true, agg));
+            if (both_tiled) ADAQP_STEP(join_now());         // as in the forward step: one tiled launch at a time
         }
         ADAQP_STEP(aggregate(d, false, msg));
         ADAQP_STEP(adaqp_quantize_pack_trace(d->out_dev,
