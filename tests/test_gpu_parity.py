@@ -492,6 +492,8 @@ def test_spmm_tiled(oracle, dim, ld):
     assert np.all(got[:, dim:zero_to] == 0.0) and np.all(got[:, zero_to:] == 7.0)
     again, _, _ = _gpu_spmm_tiled(rowptr, col, val, 0, n_rows, H, dim, ld)
     assert np.array_equal(got.view(np.uint32), again.view(np.uint32)), "runs differ"
+    none, _, _ = _gpu_spmm_tiled(rowptr, col, val, 100, 110, H, dim, ld)           # a range of empty rows only
+    assert np.all(none[100:110, :zero_to] == 0.0) and np.all(none[:100] == 7.0) and np.all(none[110:] == 7.0)
     sub, _, _ = _gpu_spmm_tiled(rowptr, col, val, 9, 120, H, dim, ld)
     assert np.all(sub[:9] == 7.0) and np.all(sub[120:] == 7.0)
     err = np.abs(sub[9:120, :dim].astype(np.float64) - want[9:120])
