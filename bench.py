@@ -24,6 +24,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+GATHER_RATE_GBPS = 25000.0      # 16-byte-per-lane gather out of L2, every XCD on its own 4 MB: measured on MI355X
+FMA_RATE_PER_S = 78.65e12       # fp32 vector FMAs per second (157.3 TFLOP/s)
 METRIC = "quantize+pack / unpack+dequant GB/s, halo SpMM edges/s, % HBM peak, 1xMI355X"
 
 
@@ -85,6 +87,35 @@ def event_time_ms(stream, fn, reps):
     return start.elapsed_time(stop) / reps
 
 
+def per_launch_ms(stream, fn, reps):
+    """Duration of each of `reps` launches from its own pair of HIP events (the kernel alone, without the gap
+    to the next launch).  Returns (median, min) in ms."""
+    import torch
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    fn(0)
+    stream.synchronize()
+    for i, (a, b) in enumerate(pairs):
+        a.record(stream)
+        fn(i + 1)
+        b.record(stream)
+    stream.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in pairs)
+    return t[len(t) // 2], t[0]
+
+
+def host_cpu():
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return model, os.cpu_count()
+
+
 def cpu_baseline(p, plan, budget_s):
     """The oracle as it stands, single thread, on a bounded sample: the whole codec (all slots) plus the
     aggregation of a contiguous block of rows sized to the time budget."""
@@ -130,6 +161,7 @@ def cpu_baseline(p, plan, budget_s):
                   f"pro-rated by the edge share",
         "quantize_pack_GBps": qb / t_q / 1e9, "unpack_dequant_GBps": db / t_d / 1e9,
         "spmm_edges_per_s": edges / t_s,
+        "host_cpu": host_cpu()[0], "host_logical_cpus": host_cpu()[1],
     }
 
 
@@ -184,8 +216,8 @@ def main():
     for name, s in sched.items():
         if name == args.schedule:
             other[name] = ms_per_step
-        elif args.all_schedules:
-            other[name] = timed_steps(s, 3, 1)
+        else:
+            other[name] = timed_steps(s, 5 if args.all_schedules else 3, 1)
 
     # ---- per-kernel breakdown: the same launches the step makes, each alone on its stream, HIP events ----
     dim = cfg.dim
@@ -211,11 +243,14 @@ def main():
     def q_warm(i):
         B.adaqp_quantize_pack(srcs[0], dim, pl.send_idx, pl.bits, pl.row_offset, 2306, packs[0], pars[0], stream=st)
 
-    t = event_time_ms(st, q_cold, reps)
-    tw = event_time_ms(st, q_warm, reps)
+    creps = max(reps, 50)                       # the codec kernels are short: 50 launches cost a millisecond
+    t = event_time_ms(st, q_cold, creps)
+    tw = event_time_ms(st, q_warm, creps)
+    t_med, t_min = per_launch_ms(st, q_cold, creps)
     kernels["quantize_pack"] = {"ms": t, "GBps": qbytes / t / 1e6, "frac_hbm": qbytes / t / 1e6 / HBM_PEAK_GBPS,
                                 "ms_warm": tw, "GBps_warm": qbytes / tw / 1e6, "bytes": qbytes,
-                                "cold_copies": n_copies}
+                                "cold_copies": n_copies, "launches": creps,
+                                "ms_median_single_launch": t_med, "ms_min_single_launch": t_min}
     if not cfg.backward:
         def d_cold(i):
             k = i % n_copies
@@ -229,10 +264,13 @@ def main():
         for k in range(n_copies):           # every copy holds valid packed data
             q_cold(k)
         st.synchronize()
-        t = event_time_ms(st, d_cold, reps)
-        tw = event_time_ms(st, d_warm, reps)
+        t = event_time_ms(st, d_cold, creps)
+        tw = event_time_ms(st, d_warm, creps)
+        t_med, t_min = per_launch_ms(st, d_cold, creps)
         kernels["unpack_dequant"] = {"ms": t, "GBps": dbytes / t / 1e6, "frac_hbm": dbytes / t / 1e6 / HBM_PEAK_GBPS,
-                                     "ms_warm": tw, "GBps_warm": dbytes / tw / 1e6, "bytes": dbytes}
+                                     "ms_warm": tw, "GBps_warm": dbytes / tw / 1e6, "bytes": dbytes,
+                                     "launches": creps, "ms_median_single_launch": t_med,
+                                     "ms_min_single_launch": t_min}
     else:
         # backward receive: the received buffer is de-quantised and added to the local rows it targets
         n_seg = pl.seg_ptr.shape[0] - 1
@@ -251,11 +289,13 @@ def main():
         for k in range(n_copies):
             q_cold(k)
         st.synchronize()
-        t = event_time_ms(st, a_cold, reps)
-        tw = event_time_ms(st, a_warm, reps)
+        t = event_time_ms(st, a_cold, creps)
+        tw = event_time_ms(st, a_warm, creps)
+        t_med, t_min = per_launch_ms(st, a_cold, creps)
         kernels["unpack_dequant_add"] = {"ms": t, "GBps": abytes / t / 1e6, "frac_hbm": abytes / t / 1e6 / HBM_PEAK_GBPS,
                                          "ms_warm": tw, "GBps_warm": abytes / tw / 1e6, "bytes": abytes,
-                                         "rows": n_seg, "messages": pl.n}
+                                         "rows": n_seg, "messages": pl.n, "launches": creps,
+                                         "ms_median_single_launch": t_med, "ms_min_single_launch": t_min}
     del srcs, packs, pars
 
     (ob, oe), (db_, de) = p.overlap_rows, p.dependent_rows
@@ -301,10 +341,24 @@ def main():
         t_m = event_time_ms(st, spmm_merge_both, max(3, sreps // 2))
         kernels["spmm_merge_path_both_launches"] = {"ms": t_m, "edges_per_s": p.nnz / t_m * 1e3,
                                                     "note": "the untiled kernel on the same rows, for comparison"}
+    # second view of the same launches: what has to cross the HBM interface at least (every entry, every row of H
+    # that is referenced and every output row once), and the step's floor when neighbour rows come out of the
+    # caches at the rate a gather kernel reaches on this part (measured with a scratch kernel: 25 TB/s when
+    # each XCD's working set fits its L2) or the fp32 FMA rate (78.6 T FMA/s) binds
+    touched = int(np.count_nonzero(np.bincount(p.col, minlength=p.feat.shape[0])))
+    compulsory = p.nnz * 8 + touched * 4 * dim + p.n_rows * 4 * dim
+    t_both = t_o + t_d
+    t_ceiling = max(compulsory / HBM_PEAK_GBPS / 1e6, p.nnz * 4 * dim / GATHER_RATE_GBPS / 1e6,
+                    p.nnz * dim / FMA_RATE_PER_S * 1e3)
+    ceilings = {"compulsory_bytes_both_launches": compulsory,
+                "frac_hbm_compulsory": compulsory / t_both / 1e6 / HBM_PEAK_GBPS,
+                "gather_rate_GBps": GATHER_RATE_GBPS, "fma_rate_per_s": FMA_RATE_PER_S,
+                "t_ceiling_ms": t_ceiling, "t_ceiling_over_t": t_ceiling / t_both}
     roofline = {"kernel": spmm_kernel, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                 "launches_per_step": 2, "avg_launch_ms": (t_o + t_d) / 2,
                 "algorithmic_bytes_per_launch": (b_o + b_d) / 2,
+                "ceilings": ceilings,
                 "note": "algorithmic bytes count one neighbour row per edge; rows re-used out of L2 / Infinity "
                         "Cache make the fraction exceed what HBM alone could deliver"
                         + ("; the tiled kernel is built for exactly that re-use (one column range of the graph "
