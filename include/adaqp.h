@@ -11,6 +11,9 @@
  *   receive side  unpack the received buffers and de-quantise them into the halo rows          (Sec. 2.3 Eq. 5)
  *   aggregation   out_v = sum over u in {v} U N(v) of alpha(u,v) * h_u as a CSR SpMM, central rows on a
  *                 second stream so that they overlap the message path      (Sec. 2.1 Eq. 3, Sec. 3.4 Fig. 7)
+ *                 - optionally straight from the packed receive buffer, or tiled over the GPU's eight L2
+ *                 caches for graphs with long rows
+ *   assignment    the next period's bit-widths from the traced beta values (host code)     (Sec. 4.2 Eq. 7-9)
  *
  * Conventions
  *   - "dev" pointers are device pointers valid on the current HIP device, "host" pointers are host memory.
