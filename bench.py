@@ -304,7 +304,7 @@ def main():
     def spmm_overlap(i):
         if L.tile_off_overlap is not None:
             B.adaqp_spmm_csr_tiled(L.rowptr, L.col, L.val, ob, oe, L.feat, dim, L.out, L.tile_off_overlap,
-                                   L.ws_overlap, stream=st)
+                                   L.ws_overlap, chunk_cols=L.tile_chunk_overlap, stream=st)
         else:
             B.adaqp_spmm_csr(L.rowptr, L.col, L.val, ob, oe, L.feat, dim, L.out, L.ws_overlap,
                              nnz_range=L.overlap_nnz, stream=st)
@@ -312,7 +312,7 @@ def main():
     def spmm_dependent(i):
         if L.tile_off_dependent is not None:
             B.adaqp_spmm_csr_tiled(L.rowptr, L.col, L.val, db_, de, L.feat, dim, L.out, L.tile_off_dependent,
-                                   L.ws_dependent, stream=st)
+                                   L.ws_dependent, chunk_cols=L.tile_chunk_dependent, stream=st)
         else:
             B.adaqp_spmm_csr(L.rowptr, L.col, L.val, db_, de, L.feat, dim, L.out, L.ws_dependent,
                              nnz_range=L.dependent_nnz, stream=st)

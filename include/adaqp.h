@@ -243,13 +243,19 @@ int adaqp_spmm_csr_packed(const int64_t *rowptr_dev, const int32_t *col_dev, con
 #define ADAQP_SPMM_TILED_SHORT_ROW 64   /* rows with fewer entries are kept whole in one tile */
 
 /* Host only.  For rows [row_begin, row_end) of a host CSR whose rows list ascending, distinct, in-range
- * columns: col_bounds_out[ADAQP_SPMM_TILES + 1] (0 = bounds[0] <= ... <= bounds[TILES] = n_cols) and
+ * columns: col_bounds_out[ADAQP_SPMM_TILES + 1] (0 = bounds[0] <= ... <= bounds[TILES] = one past the last
+ * column these rows reference, at most n_cols) and
  * tile_off_out[(row_end - row_begin) * (ADAQP_SPMM_TILES + 1)]: entry t of a row = number of its entries that
  * belong to tiles before t.  For a row of at least ADAQP_SPMM_TILED_SHORT_ROW entries that is the number of
  * entries with column < bounds[t]; a shorter row is assigned whole to tile (row - row_begin) mod
  * ADAQP_SPMM_TILES (eight segments of one or two entries each would cost more than they save).  Errors: EINVAL (unsorted / repeated / out-of-range column, bad rowptr). */
 int adaqp_plan_spmm_tiles(const int64_t *rowptr_host, const int32_t *col_host, int64_t row_begin, int64_t row_end,
                           int64_t n_cols, int32_t *col_bounds_out, int32_t *tile_off_out);
+
+/* Host only: the feature-chunk width (64 or 128 columns) to pass to adaqp_spmm_csr_tiled for a plan with these
+ * column bounds: 128 unless the widest column range times a 128-column chunk would overflow an L2.  0 on bad
+ * arguments. */
+int32_t adaqp_spmm_tiled_chunk_cols(const int32_t *col_bounds_host, int32_t dim);
 
 /* Bytes of workspace adaqp_spmm_csr_tiled needs for n_rows rows (one partial row per tile). */
 int adaqp_spmm_tiled_workspace_bytes(int64_t n_rows, int32_t dim, int64_t *bytes_out);
@@ -259,11 +265,12 @@ int adaqp_spmm_tiled_workspace_bytes(int64_t n_rows, int32_t dim, int64_t *bytes
  * with out-of-range columns; should the device arrays hold one nevertheless, it is read as column 0 with
  * coefficient 0).  A table that disagrees with rowptr is clamped to the row (wrong sums, no stray access).  The summation order is fixed by the table and the launch geometry: runs are bit-identical.
  * H and out must be line-padded (pitch a multiple of 32 floats, base 128-byte aligned); the padding of the
- * written rows is set to zero.  workspace_dev: 256-byte aligned, >= adaqp_spmm_tiled_workspace_bytes.
+ * written rows is set to zero.  chunk_cols: 64, 128 or 0 (= 128), see adaqp_spmm_tiled_chunk_cols; the result's
+ * bits depend on it.  workspace_dev: 256-byte aligned, >= adaqp_spmm_tiled_workspace_bytes.
  * Errors: EINVAL (layout, alignment, null), ESIZE (workspace too small, too many rows), EHIP. */
 int adaqp_spmm_csr_tiled(const int64_t *rowptr_dev, const int32_t *col_dev, const float *val_dev, int64_t nnz,
                          int64_t row_begin, int64_t row_end, const float *H_dev, int64_t n_cols, int64_t ldh,
-                         int32_t dim, float *out_dev, int64_t ldo, const int32_t *tile_off_dev,
+                         int32_t dim, float *out_dev, int64_t ldo, const int32_t *tile_off_dev, int32_t chunk_cols,
                          void *workspace_dev, int64_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------------- */
@@ -322,6 +329,7 @@ typedef struct adaqp_layer_desc {
                                                aggregation waits for the other one in every schedule (two tiled
                                                launches at once would share each L2 between two column ranges);
                                                the overlap with the message path stays */
+    int32_t tile_chunk_overlap, tile_chunk_dependent;   /* chunk_cols of the two tiled launches (0 = 128) */
     const int32_t *recv_seg_order_dev;  /* backward only, optional: adaqp_plan_recv_segments of halo_idx */
     const int64_t *recv_seg_ptr_dev;
     int64_t n_recv_seg;

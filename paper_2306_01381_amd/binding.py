@@ -47,6 +47,7 @@ class LayerDesc(ctypes.Structure):
         ("recv_order_dev", _vp),
         ("slot_of_row_dev", _vp),
         ("tile_off_overlap_dev", _vp), ("tile_off_dependent_dev", _vp),
+        ("tile_chunk_overlap", _i32), ("tile_chunk_dependent", _i32),
         ("recv_seg_order_dev", _vp), ("recv_seg_ptr_dev", _vp), ("n_recv_seg", _i64),
         ("n_send", _i64), ("seed", _u64),
         ("packed_dev", _vp), ("params_dev", _vp), ("alpha_sq_dev", _vp), ("beta_dev", _vp),
@@ -79,8 +80,9 @@ _SIGNATURES = {
                                       _vp, _i64, _vp, _i64, _vp]),
     "adaqp_plan_spmm_tiles": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i64, _vp, _vp]),
     "adaqp_spmm_tiled_workspace_bytes": (ctypes.c_int, [_i64, _i32, _vp]),
+    "adaqp_spmm_tiled_chunk_cols": (_i32, [_vp, _i32]),
     "adaqp_spmm_csr_tiled": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _i64, _i32, _vp, _i64,
-                                            _vp, _vp, _i64, _vp]),
+                                            _vp, _i32, _vp, _i64, _vp]),
     "adaqp_assign_bits": (ctypes.c_int, [_i64, _vp, _vp, _i32, _i32, _i32, ctypes.c_double, _vp, _vp, _vp, _vp]),
     "adaqp_plan_slot_of_row": (ctypes.c_int, [_i64, _i64, _vp, _vp]),
     "adaqp_spmm_csr_packed": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
@@ -275,15 +277,27 @@ def adaqp_spmm_tiled_workspace_bytes(n_rows: int, dim: int) -> int:
     return int(out.value)
 
 
+def adaqp_spmm_tiled_chunk_cols(col_bounds_host: np.ndarray, dim: int) -> int:
+    """Host-only.  64 or 128: the feature-chunk width for a plan with these column bounds."""
+    b = np.ascontiguousarray(col_bounds_host, dtype=np.int32)
+    if b.shape[0] != SPMM_TILES + 1:
+        raise ValueError("col_bounds needs SPMM_TILES + 1 entries")
+    c = int(lib().adaqp_spmm_tiled_chunk_cols(b.ctypes.data, dim))
+    if c == 0:
+        raise AdaqpError("adaqp_spmm_tiled_chunk_cols", -1)
+    return c
+
+
 def adaqp_spmm_csr_tiled(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, row_begin: int, row_end: int,
                          H: torch.Tensor, dim: int, out: torch.Tensor, tile_off: torch.Tensor,
-                         workspace: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+                         workspace: torch.Tensor, chunk_cols: int = 0,
+                         stream: Optional[torch.cuda.Stream] = None) -> None:
     hp, n_cols, ldh = _matrix(H, "H")
     op, _, ldo = _matrix(out, "out")
     _check(lib().adaqp_spmm_csr_tiled(_dev(rowptr, torch.int64, "rowptr"), _dev(col, torch.int32, "col"),
                                       _dev(val, torch.float32, "val"), col.numel(), row_begin, row_end,
                                       hp, n_cols, ldh, dim, op, ldo, _dev(tile_off, torch.int32, "tile_off"),
-                                      _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                      chunk_cols, _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
                                       _stream(stream)), "adaqp_spmm_csr_tiled")
 
 

@@ -188,7 +188,8 @@ int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
     const int32_t *tile_off = overlap_part ? d->tile_off_overlap_dev : d->tile_off_dependent_dev;
     if (tile_off)
         return adaqp_spmm_csr_tiled(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, d->feat_dev, d->n_feat_rows,
-                                    d->ld, d->dim, d->out_dev, d->ldo, tile_off, ws, wsb, st);
+                                    d->ld, d->dim, d->out_dev, d->ldo, tile_off,
+                                    overlap_part ? d->tile_chunk_overlap : d->tile_chunk_dependent, ws, wsb, st);
     if (!overlap_part && fused_receive(d))
         return adaqp_spmm_csr_packed(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, nz, d->feat_dev,
                                      d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, d->slot_of_row_dev,

@@ -332,7 +332,11 @@ extern "C" int adaqp_plan_spmm_tiles(const int64_t *rowptr_host, const int32_t *
             while (c < n_cols && seen < want) seen += uses[(size_t)c++];
             col_bounds_out[t] = c;
         }
-        col_bounds_out[kTiles] = (int32_t)n_cols;
+        // the last range ends after the last column that is referenced (a row range may use only part of
+        // the columns: central rows never point at halo columns)
+        int64_t last = n_cols;
+        while (last > 0 && uses[(size_t)last - 1] == 0) --last;
+        col_bounds_out[kTiles] = (int32_t)std::max<int64_t>(last, c);
     }
     for (int64_t r = row_begin; r < row_end; ++r) {
         const int32_t *cb = col_host + rowptr_host[r];
@@ -351,6 +355,18 @@ extern "C" int adaqp_plan_spmm_tiles(const int64_t *rowptr_host, const int32_t *
     return ADAQP_OK;
 }
 
+extern "C" int32_t adaqp_spmm_tiled_chunk_cols(const int32_t *col_bounds_host, int32_t dim)
+{
+    if (!col_bounds_host || dim <= 0) return 0;
+    if (dim <= 96) return 64;                               // narrower than one wide chunk
+    int64_t widest = 0;
+    for (int t = 0; t < kTiles; ++t)
+        widest = std::max<int64_t>(widest, (int64_t)col_bounds_host[t + 1] - col_bounds_host[t]);
+    // an XCD's live working set is (rows of H in its column range) x (chunk bytes); past about 5 MB the 4 MB L2
+    // misses often enough that halving the chunk pays for the extra pass over the entries
+    return widest * 512 > (int64_t)5 << 20 ? 64 : 128;
+}
+
 extern "C" int adaqp_spmm_tiled_workspace_bytes(int64_t n_rows, int32_t dim, int64_t *bytes_out)
 {
     if (!bytes_out || n_rows < 0 || dim <= 0) return ADAQP_EINVAL;
@@ -362,9 +378,10 @@ extern "C" int adaqp_spmm_tiled_workspace_bytes(int64_t n_rows, int32_t dim, int
 extern "C" int adaqp_spmm_csr_tiled(const int64_t *rowptr_dev, const int32_t *col_dev, const float *val_dev,
                                     int64_t nnz, int64_t row_begin, int64_t row_end, const float *H_dev,
                                     int64_t n_cols, int64_t ldh, int32_t dim, float *out_dev, int64_t ldo,
-                                    const int32_t *tile_off_dev, void *workspace_dev, int64_t workspace_bytes,
-                                    void *stream)
+                                    const int32_t *tile_off_dev, int32_t chunk_cols, void *workspace_dev,
+                                    int64_t workspace_bytes, void *stream)
 {
+    if (chunk_cols != 0 && chunk_cols != 64 && chunk_cols != 128) return ADAQP_EINVAL;
     if (row_begin < 0 || row_end < row_begin || nnz < 0 || dim <= 0 || ldh < dim || ldo < dim || n_cols < 0)
         return ADAQP_EINVAL;
     const int64_t n_rows = row_end - row_begin;
@@ -400,9 +417,8 @@ extern "C" int adaqp_spmm_csr_tiled(const int64_t *rowptr_dev, const int32_t *co
     a.rows_per_wave = 4;                                    // <= 64: a wave keeps its rows' segments in lanes
     const int64_t rows_per_block = (int64_t)a.rows_per_wave * kWavesPerBlock;
     a.n_row_blocks = (uint32_t)((n_rows + rows_per_block - 1) / rows_per_block);
-    // 128-column chunks (32 lanes x one vector per entry) where the rows are at least that wide; narrower
-    // matrices take 64-column chunks so that no lane idles
-    const bool wide = a.wdim >= 128;
+    // 128-column chunks (32 lanes x one vector per entry) unless the caller asks for 64 or the rows are narrower
+    const bool wide = a.wdim >= 128 && chunk_cols != 64;
     const int cw = wide ? 128 : 64;
     const int64_t n_chunks = (a.wdim + cw - 1) / cw;
     const int64_t blocks = (int64_t)a.n_row_blocks * kTiles * n_chunks;

@@ -134,16 +134,19 @@ class LayerStep:
         # aggregation tiled over the L2 caches: pays when rows are long (every row of feat re-used many times).
         # tiled=None decides per row range from the mean row length.
         self.tile_off_overlap = self.tile_off_dependent = None
+        self.tile_chunk_overlap = self.tile_chunk_dependent = 0
         ws_o = B.adaqp_spmm_workspace_bytes(oe - ob, self.overlap_nnz, cfg.dim)
         ws_d = B.adaqp_spmm_workspace_bytes(de - db, self.dependent_nnz, cfg.dim)
         if pad and tiled is not False:
             if oe > ob and (tiled or self.overlap_nnz >= self.TILED_MIN_MEAN_DEGREE * (oe - ob)):
-                _, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, ob, oe, p.feat.shape[0])
+                bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, ob, oe, p.feat.shape[0])
                 self.tile_off_overlap = torch.from_numpy(off).to(dev)
+                self.tile_chunk_overlap = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)
                 ws_o = max(ws_o, B.adaqp_spmm_tiled_workspace_bytes(oe - ob, cfg.dim))
             if de > db and (tiled or self.dependent_nnz >= self.TILED_MIN_MEAN_DEGREE * (de - db)):
-                _, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, db, de, p.feat.shape[0])
+                bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, db, de, p.feat.shape[0])
                 self.tile_off_dependent = torch.from_numpy(off).to(dev)
+                self.tile_chunk_dependent = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)
                 ws_d = max(ws_d, B.adaqp_spmm_tiled_workspace_bytes(de - db, cfg.dim))
         self.ws_overlap = torch.empty(max(ws_o, 256), dtype=torch.uint8, device=dev)
         self.ws_dependent = torch.empty(max(ws_d, 256), dtype=torch.uint8, device=dev)
@@ -179,6 +182,7 @@ class LayerStep:
                                                         and not self.backward) else None
         d.slot_of_row_dev = self.slot_of_row.data_ptr() if self.fused_receive else None
         d.tile_off_overlap_dev = None if self.tile_off_overlap is None else self.tile_off_overlap.data_ptr()
+        d.tile_chunk_overlap, d.tile_chunk_dependent = self.tile_chunk_overlap, self.tile_chunk_dependent
         d.tile_off_dependent_dev = None if (self.tile_off_dependent is None or self.fused_receive) \
             else self.tile_off_dependent.data_ptr()
         if self.backward and self.backward_receive and pl.seg_order is not None:

@@ -445,7 +445,7 @@ def test_spmm_packed_argument_checks():
 # aggregation tiled over the L2 caches (long rows)
 # ------------------------------------------------------------------------------------------------------
 
-def _gpu_spmm_tiled(rowptr, col, val, rb, re, H, dim, ldo):
+def _gpu_spmm_tiled(rowptr, col, val, rb, re, H, dim, ldo, chunk_cols=0):
     n_cols = H.shape[0]
     bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, rb, re, n_cols)
     out = torch.full((rowptr.shape[0] - 1, ldo), 7.0, dtype=torch.float32, device=DEV)
@@ -453,7 +453,7 @@ def _gpu_spmm_tiled(rowptr, col, val, rb, re, H, dim, ldo):
     ws.fill_(0xFF)                                              # NaN patterns: unread unless written first
     B.adaqp_spmm_csr_tiled(torch.from_numpy(rowptr).to(DEV), torch.from_numpy(col).to(DEV),
                            torch.from_numpy(val).to(DEV), rb, re, torch.from_numpy(H).to(DEV), dim, out,
-                           torch.from_numpy(off).to(DEV), ws)
+                           torch.from_numpy(off).to(DEV), ws, chunk_cols=chunk_cols)
     torch.cuda.synchronize()
     return out.cpu().numpy(), bounds, off
 
@@ -474,7 +474,7 @@ def test_spmm_tiled(oracle, dim, ld):
     H[:, :dim] = rng.standard_normal((n_cols, dim), dtype=np.float32)
     got, bounds, off = _gpu_spmm_tiled(rowptr, col, val, 0, n_rows, H, dim, ld)
     # the plan: tiles cover the columns, hold about an eighth of the entries each, and count each row's entries
-    assert bounds[0] == 0 and bounds[-1] == n_cols and np.all(np.diff(bounds) >= 0)
+    assert bounds[0] == 0 and bounds[-1] == col.max() + 1 and np.all(np.diff(bounds) >= 0)
     per_tile = np.histogram(col, bins=bounds.astype(np.int64))[0] if False else \
         np.array([np.count_nonzero((col >= bounds[t]) & (col < bounds[t + 1])) for t in range(B.SPMM_TILES)])
     assert per_tile.sum() == len(col) and per_tile.max() <= len(col) / B.SPMM_TILES + degs.max()
@@ -492,6 +492,11 @@ def test_spmm_tiled(oracle, dim, ld):
     assert np.all(got[:, dim:zero_to] == 0.0) and np.all(got[:, zero_to:] == 7.0)
     again, _, _ = _gpu_spmm_tiled(rowptr, col, val, 0, n_rows, H, dim, ld)
     assert np.array_equal(got.view(np.uint32), again.view(np.uint32)), "runs differ"
+    assert B.adaqp_spmm_tiled_chunk_cols(bounds, dim) == (64 if dim <= 96 else 128)     # ranges of ~110 columns
+    narrow, _, _ = _gpu_spmm_tiled(rowptr, col, val, 0, n_rows, H, dim, ld, chunk_cols=64)
+    err = np.abs(narrow[:, :dim].astype(np.float64) - want)
+    assert np.all(err <= SPMM_RTOL * mag + 1e-30), "64-column chunks"
+    assert np.all(narrow[:, dim:zero_to] == 0.0) and np.all(narrow[:, zero_to:] == 7.0)
     none, _, _ = _gpu_spmm_tiled(rowptr, col, val, 100, 110, H, dim, ld)           # a range of empty rows only
     assert np.all(none[100:110, :zero_to] == 0.0) and np.all(none[:100] == 7.0) and np.all(none[110:] == 7.0)
     sub, _, _ = _gpu_spmm_tiled(rowptr, col, val, 9, 120, H, dim, ld)

@@ -147,7 +147,7 @@ def test_plan_spmm_tiles():
     col = np.concatenate(cols).astype(np.int32)
     bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, 0, n_rows, n_cols)
     assert bounds.shape == (B.SPMM_TILES + 1,) and off.shape == (n_rows, B.SPMM_TILES + 1)
-    assert bounds[0] == 0 and bounds[-1] == n_cols and np.all(np.diff(bounds) >= 0)
+    assert bounds[0] == 0 and bounds[-1] == col.max() + 1 and np.all(np.diff(bounds) >= 0)
     def want_row(r, first_row, c, bnd):
         if len(c) >= B.SPMM_TILED_SHORT_ROW:
             return [int(np.count_nonzero(c < b)) for b in bnd]
@@ -167,7 +167,12 @@ def test_plan_spmm_tiles():
         assert off2[r - 10].tolist() == want_row(r, 10, col[rowptr[r]: rowptr[r + 1]], b2)
     # empty range, empty graph
     b3, off3 = B.adaqp_plan_spmm_tiles(rowptr, col, 5, 5, n_cols)
-    assert off3.shape == (0, B.SPMM_TILES + 1) and b3[-1] == n_cols
+    assert off3.shape == (0, B.SPMM_TILES + 1) and b3[-1] == 0
     assert B.adaqp_spmm_tiled_workspace_bytes(10, 602) == 8 * 10 * 608 * 4
+    # chunk width: 128 columns while the widest column range x 512 B stays within about 5 MB
+    even = np.arange(9, dtype=np.int32)
+    assert B.adaqp_spmm_tiled_chunk_cols(even * 7000, 602) == 128
+    assert B.adaqp_spmm_tiled_chunk_cols(even * 13000, 602) == 64
+    assert B.adaqp_spmm_tiled_chunk_cols(even * 7000, 64) == 64
     with pytest.raises(B.AdaqpError):
         B.adaqp_plan_spmm_tiles(np.array([0, 2], np.int64), np.array([5, 5], np.int32), 0, 1, 8)   # repeated column
