@@ -241,6 +241,11 @@ int adaqp_spmm_csr_packed(const int64_t *rowptr_dev, const int32_t *col_dev, con
  * with equal entry counts, once per graph, on the host.  Line-padded layout only. */
 #define ADAQP_SPMM_TILES 8
 #define ADAQP_SPMM_TILED_SHORT_ROW 64   /* rows with fewer entries are kept whole in one tile */
+#define ADAQP_SPMM_TILED_MIN_MEAN_ROW 128    /* mean entries per row from which adaqp_spmm_tiled_pays says yes */
+
+/* Host only: 1 if a row range with n_rows rows and nnz entries is worth aggregating with adaqp_spmm_csr_tiled
+ * rather than adaqp_spmm_csr (long rows: every row of H re-used many times), else 0. */
+int32_t adaqp_spmm_tiled_pays(int64_t n_rows, int64_t nnz);
 
 /* Host only.  For rows [row_begin, row_end) of a host CSR whose rows list ascending, distinct, in-range
  * columns: col_bounds_out[ADAQP_SPMM_TILES + 1] (0 = bounds[0] <= ... <= bounds[TILES] = one past the last

@@ -80,6 +80,7 @@ _SIGNATURES = {
                                       _vp, _i64, _vp, _i64, _vp]),
     "adaqp_plan_spmm_tiles": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i64, _vp, _vp]),
     "adaqp_spmm_tiled_workspace_bytes": (ctypes.c_int, [_i64, _i32, _vp]),
+    "adaqp_spmm_tiled_pays": (_i32, [_i64, _i64]),
     "adaqp_spmm_tiled_chunk_cols": (_i32, [_vp, _i32]),
     "adaqp_spmm_csr_tiled": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _i64, _i32, _vp, _i64,
                                             _vp, _i32, _vp, _i64, _vp]),
@@ -275,6 +276,11 @@ def adaqp_spmm_tiled_workspace_bytes(n_rows: int, dim: int) -> int:
     out = ctypes.c_int64(0)
     _check(lib().adaqp_spmm_tiled_workspace_bytes(n_rows, dim, ctypes.byref(out)), "adaqp_spmm_tiled_workspace_bytes")
     return int(out.value)
+
+
+def adaqp_spmm_tiled_pays(n_rows: int, nnz: int) -> bool:
+    """Host-only.  True if a row range of this shape is better served by adaqp_spmm_csr_tiled."""
+    return bool(lib().adaqp_spmm_tiled_pays(n_rows, nnz))
 
 
 def adaqp_spmm_tiled_chunk_cols(col_bounds_host: np.ndarray, dim: int) -> int:

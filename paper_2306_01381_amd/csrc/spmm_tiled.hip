@@ -355,6 +355,14 @@ extern "C" int adaqp_plan_spmm_tiles(const int64_t *rowptr_host, const int32_t *
     return ADAQP_OK;
 }
 
+extern "C" int32_t adaqp_spmm_tiled_pays(int64_t n_rows, int64_t nnz)
+{
+    // a partial row per (row, tile) with entries, written and read back, against one neighbour row per entry
+    // fetched 2-3 times faster: worth it from a mean row length of about a hundred entries (measured: wins
+    // at 440-520, loses at 9-43)
+    return n_rows > 0 && nnz >= ADAQP_SPMM_TILED_MIN_MEAN_ROW * n_rows ? 1 : 0;
+}
+
 extern "C" int32_t adaqp_spmm_tiled_chunk_cols(const int32_t *col_bounds_host, int32_t dim)
 {
     if (!col_bounds_host || dim <= 0) return 0;

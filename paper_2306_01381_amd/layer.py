@@ -87,8 +87,6 @@ def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
 
 
 class LayerStep:
-    TILED_MIN_MEAN_DEGREE = 128     # below this the per-(row, tile) partial sums cost more than the L2 re-use saves
-
     def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False,
                  backward_receive: bool = True, trace: bool = True, fused_receive: bool = False,
                  tiled: Optional[bool] = None):
@@ -132,18 +130,18 @@ class LayerStep:
         self.overlap_nnz = int(p.rowptr[oe] - p.rowptr[ob])
         self.dependent_nnz = int(p.rowptr[de] - p.rowptr[db])
         # aggregation tiled over the L2 caches: pays when rows are long (every row of feat re-used many times).
-        # tiled=None decides per row range from the mean row length.
+        # tiled=None lets the library decide per row range (adaqp_spmm_tiled_pays: mean row length).
         self.tile_off_overlap = self.tile_off_dependent = None
         self.tile_chunk_overlap = self.tile_chunk_dependent = 0
         ws_o = B.adaqp_spmm_workspace_bytes(oe - ob, self.overlap_nnz, cfg.dim)
         ws_d = B.adaqp_spmm_workspace_bytes(de - db, self.dependent_nnz, cfg.dim)
         if pad and tiled is not False:
-            if oe > ob and (tiled or self.overlap_nnz >= self.TILED_MIN_MEAN_DEGREE * (oe - ob)):
+            if oe > ob and (tiled or B.adaqp_spmm_tiled_pays(oe - ob, self.overlap_nnz)):
                 bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, ob, oe, p.feat.shape[0])
                 self.tile_off_overlap = torch.from_numpy(off).to(dev)
                 self.tile_chunk_overlap = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)
                 ws_o = max(ws_o, B.adaqp_spmm_tiled_workspace_bytes(oe - ob, cfg.dim))
-            if de > db and (tiled or self.dependent_nnz >= self.TILED_MIN_MEAN_DEGREE * (de - db)):
+            if de > db and (tiled or B.adaqp_spmm_tiled_pays(de - db, self.dependent_nnz)):
                 bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, db, de, p.feat.shape[0])
                 self.tile_off_dependent = torch.from_numpy(off).to(dev)
                 self.tile_chunk_dependent = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)

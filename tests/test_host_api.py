@@ -169,6 +169,8 @@ def test_plan_spmm_tiles():
     b3, off3 = B.adaqp_plan_spmm_tiles(rowptr, col, 5, 5, n_cols)
     assert off3.shape == (0, B.SPMM_TILES + 1) and b3[-1] == 0
     assert B.adaqp_spmm_tiled_workspace_bytes(10, 602) == 8 * 10 * 608 * 4
+    assert B.adaqp_spmm_tiled_pays(28000, 12_763_658) and B.adaqp_spmm_tiled_pays(30000, 15_478_947)   # c1
+    assert not B.adaqp_spmm_tiled_pays(306000, 7_680_000) and not B.adaqp_spmm_tiled_pays(0, 0)          # c2, empty
     # chunk width: 128 columns while the widest column range x 512 B stays within about 5 MB
     even = np.arange(9, dtype=np.int32)
     assert B.adaqp_spmm_tiled_chunk_cols(even * 7000, 602) == 128
