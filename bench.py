@@ -323,6 +323,7 @@ def main():
         B.adaqp_spmm_csr(L.rowptr, L.col, L.val, db_, de, L.feat, dim, L.out, L.ws_dependent,
                          nnz_range=L.dependent_nnz, stream=st)
 
+    tiled_both = L.tile_off_overlap is not None and L.tile_off_dependent is not None
     sreps = max(3, min(reps, int(2000 / max(ms_per_step, 0.05))))
     t_o = event_time_ms(st, spmm_overlap, sreps)
     t_d = event_time_ms(st, spmm_dependent, sreps)
@@ -333,6 +334,28 @@ def main():
                          "GBps": b_o / t_o / 1e6, "frac_hbm": b_o / t_o / 1e6 / HBM_PEAK_GBPS}
     kernels[names[1]] = {"ms": t_d, "edges": L.dependent_nnz, "edges_per_s": L.dependent_nnz / t_d * 1e3,
                          "GBps": b_d / t_d / 1e6, "frac_hbm": b_d / t_d / 1e6 / HBM_PEAK_GBPS}
+    # the whole row range in one launch (what a step without the central / marginal split would run)
+    all_rows = p.n_rows
+    if tiled_both:
+        bounds_all, off_all = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, 0, all_rows, p.feat.shape[0])
+        off_all_dev = torch.from_numpy(off_all).to(dev)
+        chunk_all = B.adaqp_spmm_tiled_chunk_cols(bounds_all, dim)
+        ws_all = torch.empty(B.adaqp_spmm_tiled_workspace_bytes(all_rows, dim), dtype=torch.uint8, device=dev)
+
+        def spmm_all(i):
+            B.adaqp_spmm_csr_tiled(L.rowptr, L.col, L.val, 0, all_rows, L.feat, dim, L.out, off_all_dev, ws_all,
+                                   chunk_cols=chunk_all, stream=st)
+    else:
+        ws_all = torch.empty(max(B.adaqp_spmm_workspace_bytes(all_rows, p.nnz, dim), 256), dtype=torch.uint8,
+                             device=dev)
+
+        def spmm_all(i):
+            B.adaqp_spmm_csr(L.rowptr, L.col, L.val, 0, all_rows, L.feat, dim, L.out, ws_all, nnz_range=p.nnz,
+                             stream=st)
+    t_all = event_time_ms(st, spmm_all, sreps)
+    kernels["spmm_all_rows_one_launch"] = {"ms": t_all, "edges": p.nnz, "edges_per_s": p.nnz / t_all * 1e3,
+                                           "kernel": "tiled" if tiled_both else "merge-path"}
+    del ws_all
     # dominant kernel: the merge-path SpMM, two launches per step; per-launch averages
     achieved = (b_o + b_d) / (t_o + t_d) / 1e6
     tiled = L.tile_off_overlap is not None or L.tile_off_dependent is not None
