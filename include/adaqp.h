@@ -358,6 +358,10 @@ typedef struct adaqp_layer_desc {
  * results.  Errors: EINVAL, ESIZE, EHIP. */
 int adaqp_layer_step(const adaqp_layer_desc *desc_host);
 
+/* sizeof(adaqp_layer_desc) as this library was built: lets a binding in another language check its mirror of the
+ * struct before the first call. */
+int64_t adaqp_layer_desc_bytes(void);
+
 #ifdef __cplusplus
 }
 #endif

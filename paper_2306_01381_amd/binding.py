@@ -89,6 +89,7 @@ _SIGNATURES = {
     "adaqp_spmm_csr_packed": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
                                              _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "adaqp_layer_step": (ctypes.c_int, [ctypes.POINTER(LayerDesc)]),
+    "adaqp_layer_desc_bytes": (_i64, []),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -104,6 +105,9 @@ def lib() -> ctypes.CDLL:
             fn = getattr(L, name)
             fn.restype = res
             fn.argtypes = args
+        if int(L.adaqp_layer_desc_bytes()) != ctypes.sizeof(LayerDesc):
+            raise ImportError(f"LayerDesc ({ctypes.sizeof(LayerDesc)} bytes) does not mirror adaqp_layer_desc "
+                              f"({int(L.adaqp_layer_desc_bytes())} bytes) of {LIB_PATH}: rebuild the library")
         _lib = L
     return _lib
 

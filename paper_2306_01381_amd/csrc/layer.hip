@@ -212,6 +212,8 @@ int loop_back(const adaqp_layer_desc *d, hipStream_t st)
 
 }  // namespace
 
+extern "C" int64_t adaqp_layer_desc_bytes(void) { return (int64_t)sizeof(adaqp_layer_desc); }
+
 extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
 {
     int rc = check_desc(d);

@@ -178,3 +178,8 @@ def test_plan_spmm_tiles():
     assert B.adaqp_spmm_tiled_chunk_cols(even * 7000, 64) == 64
     with pytest.raises(B.AdaqpError):
         B.adaqp_plan_spmm_tiles(np.array([0, 2], np.int64), np.array([5, 5], np.int32), 0, 1, 8)   # repeated column
+
+
+def test_layer_desc_mirror_matches_the_library():
+    import ctypes
+    assert int(B.lib().adaqp_layer_desc_bytes()) == ctypes.sizeof(B.LayerDesc)
