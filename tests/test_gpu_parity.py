@@ -505,6 +505,50 @@ def test_spmm_tiled(oracle, dim, ld):
     assert np.all(err <= SPMM_RTOL * mag[9:120] + 1e-30)
 
 
+def test_spmm_tiled_random_shapes(oracle):
+    """Seeded sweep over small shapes: fewer columns than tiles, single rows, one dense row, ragged widths."""
+    rng = np.random.default_rng(4242)
+    dims = [1, 5, 31, 32, 33, 64, 65, 127, 128, 129, 200, 256, 300, 602]
+    for case in range(24):
+        n_rows = int(rng.choice([1, 2, 3, 15, 16, 17, 100, 257]))
+        n_cols = int(rng.choice([1, 2, 7, 8, 9, 70, 500, 1500]))
+        dim = int(rng.choice(dims))
+        ld = (dim + 31) // 32 * 32
+        kind = case % 4
+        if kind == 0:
+            degs = rng.integers(0, min(n_cols, 200) + 1, size=n_rows)
+        elif kind == 1:
+            degs = np.full(n_rows, n_cols)                              # dense
+        elif kind == 2:
+            degs = np.zeros(n_rows, dtype=np.int64)
+            degs[rng.integers(0, n_rows)] = n_cols                      # one full row, the rest empty
+        else:
+            degs = rng.integers(0, 3, size=n_rows)                      # nearly empty
+        _say(f"tiled spmm case {case}: rows {n_rows} cols {n_cols} dim {dim} kind {kind}")
+        rowptr, col, val = _random_graph(rng, n_rows, n_cols, degs)
+        H = np.full((n_cols, ld), np.nan, dtype=np.float32)
+        H[:, :dim] = rng.standard_normal((n_cols, dim), dtype=np.float32)
+        want, mag = oracle.spmm_csr(rowptr, col, val, 0, n_rows, np.ascontiguousarray(H[:, :dim]), dim)
+        for chunk in (0, 64):
+            if len(col) == 0:
+                # no entries at all: col / val may not even exist; the call only has to zero the rows
+                got = torch.full((n_rows, ld), 7.0, dtype=torch.float32, device=DEV)
+                off = np.zeros((n_rows, B.SPMM_TILES + 1), dtype=np.int32)
+                ws = torch.empty(max(B.adaqp_spmm_tiled_workspace_bytes(n_rows, dim), 256), dtype=torch.uint8,
+                                 device=DEV)
+                B.adaqp_spmm_csr_tiled(torch.from_numpy(rowptr).to(DEV), torch.zeros(1, dtype=torch.int32, device=DEV)[:0],
+                                       torch.zeros(1, dtype=torch.float32, device=DEV)[:0], 0, n_rows,
+                                       torch.from_numpy(H).to(DEV), dim, got, torch.from_numpy(off).to(DEV), ws,
+                                       chunk_cols=chunk)
+                torch.cuda.synchronize()
+                got = got.cpu().numpy()
+            else:
+                got, _, _ = _gpu_spmm_tiled(rowptr, col, val, 0, n_rows, H, dim, ld, chunk_cols=chunk)
+            err = np.abs(got[:, :dim].astype(np.float64) - want)
+            assert np.all(err <= SPMM_RTOL * mag + 1e-30), f"case {case} chunk {chunk}"
+            assert np.all(got[:, dim:] == 0.0), f"case {case}: row padding"
+
+
 def test_spmm_tiled_rejects_what_it_cannot_do():
     rowptr = np.array([0, 2], dtype=np.int64)
     with pytest.raises(B.AdaqpError):
