@@ -382,6 +382,10 @@ def main():
                 "launches_per_step": 2, "avg_launch_ms": (t_o + t_d) / 2,
                 "algorithmic_bytes_per_launch": (b_o + b_d) / 2,
                 "ceilings": ceilings,
+                "binding_limit": ("gather rate of the CUs' vector-memory pipeline out of L2 (22-25 TB/s measured), "
+                                  "not HBM: most neighbour rows hit in the XCD's L2" if tiled else
+                                  "the path behind L2 (fabric / Infinity Cache / HBM, about 7.5 TB/s measured) "
+                                  "for the rows that miss L2"),
                 "note": "algorithmic bytes count one neighbour row per edge; rows re-used out of L2 / Infinity "
                         "Cache make the fraction exceed what HBM alone could deliver"
                         + ("; the tiled kernel is built for exactly that re-use (one column range of the graph "
