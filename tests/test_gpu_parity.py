@@ -756,3 +756,33 @@ def test_layer_step_with_tiled_aggregation(oracle, name):
         if first is None:
             first = out
         assert np.array_equal(out.view(np.uint32), first.view(np.uint32)), "schedules disagree"
+
+
+@pytest.mark.parametrize("schedule_name", ["serial", "isolated"])
+def test_layer_step_captured_in_a_graph(schedule_name):
+    """The step allocates nothing and clears nothing with memset, so it can be captured into a HIP graph; every
+    replay (with eager work and synchronisations in between) must give the bits of the eager step."""
+    schedule = {"serial": B.SERIAL, "isolated": B.ISOLATED}[schedule_name]
+    p = make_partition(CONFIGS["c0"])
+    cfg = p.cfg
+    L = LayerStep(p, DEV, seed=99)
+    L.run(schedule)
+    L.synchronize()
+    want_out = L.out.clone()
+    want_feat = L.feat.clone()
+    want_packed = L.recv_packed.clone()
+    desc = L.desc(schedule)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=L.stream_msg):
+        B.adaqp_layer_step(desc)
+    for replay in range(3):
+        L.out.fill_(float("nan"))                                   # eager work between the replays
+        L.feat[cfg.n_local: cfg.n_local + cfg.n_send] = float("nan")
+        L.recv_packed.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(L.recv_packed, want_packed), f"replay {replay}: packed bytes"
+        assert torch.equal(L.feat.view(torch.int32), want_feat.view(torch.int32)), f"replay {replay}: halo rows"
+        assert torch.equal(L.out.view(torch.int32), want_out.view(torch.int32)), f"replay {replay}: aggregate"
