@@ -212,6 +212,21 @@ def main():
         fused = {"ms_per_step": ms_fused, "value": p.nnz / ms_fused * 1e3, "unit": "edges/s",
                  "note": "adaqp_spmm_csr_packed for the marginal rows, no adaqp_unpack_dequant launch; "
                          "output bit-identical to the step with the untiled aggregation"}
+    # the same step captured into a HIP graph and replayed (no per-launch host work between the kernels)
+    desc_g = L.desc(sched[args.schedule])
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=L.stream_msg):
+        B.adaqp_layer_step(desc_g)
+    for _ in range(args.warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t_g = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_graph = (time.perf_counter() - t_g) * 1e3 / args.steps
+    del graph
     other = {}
     for name, s in sched.items():
         if name == args.schedule:
@@ -400,6 +415,7 @@ def main():
                    "packed_bytes": pl.packed_bytes, "direction": p.meta["direction"],
                    "schedule": args.schedule, "seed": cfg.seed},
         "ms_per_step_by_schedule": other,
+        "ms_per_step_graph_replay": ms_graph,
         "fused_receive_variant": fused,
         "kernels": kernels,
         "roofline": roofline,
