@@ -279,6 +279,70 @@ int adaqp_spmm_csr_tiled(const int64_t *rowptr_dev, const int32_t *col_dev, cons
                          void *workspace_dev, int64_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------------- */
+/* Dense panels for the longest rows of such a graph.  In a power-law graph (the degree shape of the paper's
+ * densest dataset, Sec. 5) a few thousand rows hold most of the entries, and any 32 of them share most of their
+ * columns.  The host gathers such rows into panels of ADAQP_SPMM_PANEL_ROWS rows: per panel the sorted list of
+ * the distinct columns its rows reference and a dense [columns][32] table of coefficients alpha(u, v) (0 where a
+ * row lacks the column).  The same sum of Sec. 2.1 Eq. 3 is then a small dense product per panel: each row of H
+ * is fetched once per panel instead of once per entry, and the multiply-adds run on the fp32 matrix cores.
+ * The rows taken into panels are struck from the tile table, so adaqp_spmm_csr_tiled covers the remaining rows
+ * and adaqp_spmm_csr_panels these; call the tiled one first (it writes zeros to the struck rows).
+ * A zero coefficient times a non-finite H entry is NaN: H must be finite (as everywhere in this library), or a
+ * non-finite row of H reaches all rows of the panels that list its column. */
+#define ADAQP_SPMM_PANEL_ROWS 32
+#define ADAQP_SPMM_PANEL_MIN_ROW 2048     /* default: rows with at least this many entries go into panels */
+#define ADAQP_SPMM_PANEL_PIECE_COLS 1024  /* default: panel columns per piece of work (a multiple of 8) */
+
+/* Device side of a panel plan for one row range.  All arrays are device copies of what adaqp_plan_spmm_panels
+ * wrote; the struct itself lives in host memory and is read during the call only. */
+typedef struct adaqp_spmm_panels {
+    int32_t n_panels;                   /* 0: no panels, the struct is ignored */
+    int32_t n_per_tile;                 /* pieces per tile list */
+    int64_t n_groups;                   /* groups of 8 panel columns */
+    int64_t n_panel_pieces;             /* pieces in use */
+    const int32_t *panel_rows_dev;      /* [n_panels * 32] row of out per panel row, -1 = unused */
+    const int32_t *pcol_dev;            /* [n_groups][2][4]: column of H for panel column 8g + 2u + h at [g][h][u] */
+    const float   *palpha_dev;          /* [n_groups][64][4]: coefficient of panel column 8g + 2u + h, panel row m
+                                           at [g][32h + m][u] */
+    const int32_t *piece_dev;           /* [ADAQP_SPMM_TILES][n_per_tile][2]: first and end group; equal = unused */
+    const int32_t *panel_piece_ptr_dev; /* [n_panels + 1] into panel_piece */
+    const int32_t *panel_piece_dev;     /* [n_panel_pieces] piece numbers tile * n_per_tile + i, ascending per panel */
+} adaqp_spmm_panels;
+
+/* Host only.  Plans the panels of rows [row_begin, row_end) of a host CSR (ascending, distinct, in-range columns
+ * per row) with at least min_row_len entries; col_bounds_host is adaqp_plan_spmm_tiles' output for the same
+ * range (the pieces of a panel follow the same eight column ranges, so that each L2 keeps seeing one range).
+ * Rows are taken in order of descending length (ties: ascending row), 32 per panel; the last panel may be
+ * partly filled.  Every (panel, tile) column list is padded to a multiple of 8 with coefficient 0 and cut
+ * into pieces of piece_cols columns.
+ * Call twice: first with panel_rows_out NULL, which only fills sizes_out[5] = { rows taken, n_panels,
+ * n_groups, n_per_tile, n_panel_pieces }; then with arrays of those sizes (layouts as in adaqp_spmm_panels).
+ * tile_off_inout (may be NULL): adaqp_plan_spmm_tiles' table for the range; on the filling call the rows taken
+ * get all-zero entries, i.e. adaqp_spmm_csr_tiled skips them.
+ * Errors: EINVAL (bad CSR, min_row_len < 1, piece_cols not a positive multiple of 8), ESIZE (sizes beyond
+ * 2^31 - 1). */
+int adaqp_plan_spmm_panels(const int64_t *rowptr_host, const int32_t *col_host, const float *val_host,
+                           int64_t row_begin, int64_t row_end, int64_t n_cols, const int32_t *col_bounds_host,
+                           int32_t min_row_len, int32_t piece_cols, int64_t *sizes_out,
+                           int32_t *tile_off_inout, int32_t *panel_rows_out, int32_t *pcol_out, float *palpha_out,
+                           int32_t *piece_out, int32_t *panel_piece_ptr_out, int32_t *panel_piece_out);
+
+/* Bytes of workspace adaqp_spmm_csr_panels needs (one [32][dim padded to lines] partial per piece slot). */
+int adaqp_spmm_panels_workspace_bytes(int32_t n_per_tile, int32_t dim, int64_t *bytes_out);
+
+/* out[r, 0:dim] = sum_j val[j] * H[col[j], 0:dim] (Sec. 2.1 Eq. 3) for the rows r listed in the panels; other
+ * rows of out are not touched.  Products and sums in fp32 on the matrix cores (v_mfma_f32_32x32x2_f32); the
+ * summation order is fixed by the plan: per piece in panel-column order, then the pieces of a panel in ascending
+ * piece number, so runs are bit-identical.  H and out line-padded as for adaqp_spmm_csr_tiled; padding of the
+ * written rows is set to zero.  A column number outside [0, n_cols) in pcol_dev is clamped into range and a
+ * group number outside [0, n_groups] likewise (wrong sums, no stray access); panel rows outside [row_begin,
+ * row_end) are skipped.  workspace_dev: 256-byte aligned, >= adaqp_spmm_panels_workspace_bytes.
+ * Errors: EINVAL (layout, alignment, null, negative sizes), ESIZE (workspace too small), EHIP. */
+int adaqp_spmm_csr_panels(const adaqp_spmm_panels *panels_host, int64_t row_begin, int64_t row_end,
+                          const float *H_dev, int64_t n_cols, int64_t ldh, int32_t dim, float *out_dev, int64_t ldo,
+                          void *workspace_dev, int64_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------------- */
 /* One layer's aggregation step with the message path overlapped (Sec. 3.1, Sec. 3.4 Fig. 7).             */
 /* ---------------------------------------------------------------------------------------------------- */
 
@@ -335,6 +399,9 @@ typedef struct adaqp_layer_desc {
                                                launches at once would share each L2 between two column ranges);
                                                the overlap with the message path stays */
     int32_t tile_chunk_overlap, tile_chunk_dependent;   /* chunk_cols of the two tiled launches (0 = 128) */
+    adaqp_spmm_panels panels_overlap;       /* optional (n_panels = 0: none): adaqp_plan_spmm_panels of the two row */
+    adaqp_spmm_panels panels_dependent;     /* ranges; only with that range's tile table.  The range's workspace must
+                                               hold adaqp_spmm_panels_workspace_bytes as well */
     const int32_t *recv_seg_order_dev;  /* backward only, optional: adaqp_plan_recv_segments of halo_idx */
     const int64_t *recv_seg_ptr_dev;
     int64_t n_recv_seg;

@@ -34,6 +34,15 @@ class AdaqpError(RuntimeError):
         super().__init__(f"{where}: {msg} ({status})")
 
 
+class SpmmPanels(ctypes.Structure):
+    """Mirror of struct adaqp_spmm_panels."""
+    _fields_ = [
+        ("n_panels", _i32), ("n_per_tile", _i32), ("n_groups", _i64), ("n_panel_pieces", _i64),
+        ("panel_rows_dev", _vp), ("pcol_dev", _vp), ("palpha_dev", _vp), ("piece_dev", _vp),
+        ("panel_piece_ptr_dev", _vp), ("panel_piece_dev", _vp),
+    ]
+
+
 class LayerDesc(ctypes.Structure):
     """Mirror of struct adaqp_layer_desc."""
     _fields_ = [
@@ -48,6 +57,7 @@ class LayerDesc(ctypes.Structure):
         ("slot_of_row_dev", _vp),
         ("tile_off_overlap_dev", _vp), ("tile_off_dependent_dev", _vp),
         ("tile_chunk_overlap", _i32), ("tile_chunk_dependent", _i32),
+        ("panels_overlap", SpmmPanels), ("panels_dependent", SpmmPanels),
         ("recv_seg_order_dev", _vp), ("recv_seg_ptr_dev", _vp), ("n_recv_seg", _i64),
         ("n_send", _i64), ("seed", _u64),
         ("packed_dev", _vp), ("params_dev", _vp), ("alpha_sq_dev", _vp), ("beta_dev", _vp),
@@ -84,6 +94,11 @@ _SIGNATURES = {
     "adaqp_spmm_tiled_chunk_cols": (_i32, [_vp, _i32]),
     "adaqp_spmm_csr_tiled": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _i64, _i32, _vp, _i64,
                                             _vp, _i32, _vp, _i64, _vp]),
+    "adaqp_plan_spmm_panels": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _vp, _vp,
+                                              _vp, _vp, _vp, _vp]),
+    "adaqp_spmm_panels_workspace_bytes": (ctypes.c_int, [_i32, _i32, _vp]),
+    "adaqp_spmm_csr_panels": (ctypes.c_int, [ctypes.POINTER(SpmmPanels), _i64, _i64, _vp, _i64, _i64, _i32, _vp,
+                                             _i64, _vp, _i64, _vp]),
     "adaqp_assign_bits": (ctypes.c_int, [_i64, _vp, _vp, _i32, _i32, _i32, ctypes.c_double, _vp, _vp, _vp, _vp]),
     "adaqp_plan_slot_of_row": (ctypes.c_int, [_i64, _i64, _vp, _vp]),
     "adaqp_spmm_csr_packed": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
@@ -262,6 +277,9 @@ def adaqp_spmm_csr(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, r
 
 SPMM_TILES = 8
 SPMM_TILED_SHORT_ROW = 64
+SPMM_PANEL_ROWS = 32
+SPMM_PANEL_MIN_ROW = 2048
+SPMM_PANEL_PIECE_COLS = 1024
 
 
 def adaqp_plan_spmm_tiles(rowptr_host: np.ndarray, col_host: np.ndarray, row_begin: int, row_end: int,
@@ -296,6 +314,87 @@ def adaqp_spmm_tiled_chunk_cols(col_bounds_host: np.ndarray, dim: int) -> int:
     if c == 0:
         raise AdaqpError("adaqp_spmm_tiled_chunk_cols", -1)
     return c
+
+
+def adaqp_plan_spmm_panels(rowptr_host: np.ndarray, col_host: np.ndarray, val_host: np.ndarray, row_begin: int,
+                           row_end: int, n_cols: int, col_bounds_host: np.ndarray,
+                           tile_off: Optional[np.ndarray] = None, min_row_len: int = SPMM_PANEL_MIN_ROW,
+                           piece_cols: int = SPMM_PANEL_PIECE_COLS) -> Optional[dict]:
+    """Host-only.  Returns None when no row of the range has min_row_len entries, else a dict of host arrays
+    (panel_rows, pcol, palpha, piece, panel_piece_ptr, panel_piece) and sizes (n_rows_taken, n_panels, n_groups,
+    n_per_tile, n_panel_pieces).  tile_off (the C-contiguous int32 table of adaqp_plan_spmm_tiles for the same
+    range) is changed in place: the rows taken are struck from it."""
+    rowptr = np.ascontiguousarray(rowptr_host, dtype=np.int64)
+    col = np.ascontiguousarray(col_host, dtype=np.int32)
+    val = np.ascontiguousarray(val_host, dtype=np.float32)
+    bounds = np.ascontiguousarray(col_bounds_host, dtype=np.int32)
+    if bounds.shape[0] != SPMM_TILES + 1:
+        raise ValueError("col_bounds needs SPMM_TILES + 1 entries")
+    if tile_off is not None:
+        if tile_off.dtype != np.int32 or not tile_off.flags.c_contiguous or \
+                tile_off.shape != (max(row_end - row_begin, 0), SPMM_TILES + 1):
+            raise ValueError("tile_off must be the C-contiguous int32 table of adaqp_plan_spmm_tiles for this range")
+    sizes = np.zeros(5, dtype=np.int64)
+    args = (rowptr.ctypes.data, col.ctypes.data, val.ctypes.data, row_begin, row_end, n_cols, bounds.ctypes.data,
+            min_row_len, piece_cols, sizes.ctypes.data)
+    _check(lib().adaqp_plan_spmm_panels(*args, None, None, None, None, None, None, None), "adaqp_plan_spmm_panels")
+    taken, n_panels, n_groups, n_per_tile, n_pieces = (int(x) for x in sizes)
+    if taken == 0:
+        return None
+    plan = {
+        "n_rows_taken": taken, "n_panels": n_panels, "n_groups": n_groups, "n_per_tile": n_per_tile,
+        "n_panel_pieces": n_pieces,
+        "panel_rows": np.empty(n_panels * SPMM_PANEL_ROWS, dtype=np.int32),
+        "pcol": np.empty((n_groups, 2, 4), dtype=np.int32),
+        "palpha": np.empty((n_groups, 64, 4), dtype=np.float32),
+        "piece": np.empty((SPMM_TILES, n_per_tile, 2), dtype=np.int32),
+        "panel_piece_ptr": np.empty(n_panels + 1, dtype=np.int32),
+        "panel_piece": np.empty(n_pieces, dtype=np.int32),
+    }
+    _check(lib().adaqp_plan_spmm_panels(*args, None if tile_off is None else tile_off.ctypes.data,
+                                        plan["panel_rows"].ctypes.data, plan["pcol"].ctypes.data,
+                                        plan["palpha"].ctypes.data, plan["piece"].ctypes.data,
+                                        plan["panel_piece_ptr"].ctypes.data, plan["panel_piece"].ctypes.data),
+           "adaqp_plan_spmm_panels")
+    return plan
+
+
+class DevicePanels:
+    """Device copies of a panel plan plus the struct the C calls take.  Keeps the tensors alive."""
+
+    def __init__(self, plan: Optional[dict], device="cuda"):
+        self.c = SpmmPanels()
+        self.tensors = {}
+        self.n_per_tile = 0
+        if plan is None:
+            return
+        for k in ("panel_rows", "pcol", "palpha", "piece", "panel_piece_ptr", "panel_piece"):
+            self.tensors[k] = torch.from_numpy(plan[k]).to(device)
+        t = self.tensors
+        self.n_per_tile = plan["n_per_tile"]
+        self.c = SpmmPanels(plan["n_panels"], plan["n_per_tile"], plan["n_groups"], plan["n_panel_pieces"],
+                            t["panel_rows"].data_ptr(), t["pcol"].data_ptr(), t["palpha"].data_ptr(),
+                            t["piece"].data_ptr(), t["panel_piece_ptr"].data_ptr(), t["panel_piece"].data_ptr())
+
+    def __bool__(self) -> bool:
+        return self.c.n_panels > 0
+
+
+def adaqp_spmm_panels_workspace_bytes(n_per_tile: int, dim: int) -> int:
+    out = ctypes.c_int64(0)
+    _check(lib().adaqp_spmm_panels_workspace_bytes(n_per_tile, dim, ctypes.byref(out)),
+           "adaqp_spmm_panels_workspace_bytes")
+    return int(out.value)
+
+
+def adaqp_spmm_csr_panels(panels: DevicePanels, row_begin: int, row_end: int, H: torch.Tensor, dim: int,
+                          out: torch.Tensor, workspace: torch.Tensor,
+                          stream: Optional[torch.cuda.Stream] = None) -> None:
+    hp, n_cols, ldh = _matrix(H, "H")
+    op, _, ldo = _matrix(out, "out")
+    _check(lib().adaqp_spmm_csr_panels(ctypes.byref(panels.c), row_begin, row_end, hp, n_cols, ldh, dim, op, ldo,
+                                       _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                       _stream(stream)), "adaqp_spmm_csr_panels")
 
 
 def adaqp_spmm_csr_tiled(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, row_begin: int, row_end: int,

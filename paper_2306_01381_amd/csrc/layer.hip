@@ -163,6 +163,16 @@ int check_desc(const adaqp_layer_desc *d)
             return ADAQP_EINVAL;
         if (d->direction == ADAQP_FORWARD && !d->halo_idx_dev) return ADAQP_EINVAL;
     }
+    for (int part = 0; part < 2; ++part) {
+        const adaqp_spmm_panels *p = part ? &d->panels_overlap : &d->panels_dependent;
+        const int32_t *tile_off = part ? d->tile_off_overlap_dev : d->tile_off_dependent_dev;
+        if (p->n_panels < 0 || p->n_per_tile < 0 || p->n_groups < 0 || p->n_panel_pieces < 0) return ADAQP_EINVAL;
+        if (p->n_panels == 0) continue;
+        if (!tile_off) return ADAQP_EINVAL;                 // panels complement a tile table, never the merge path
+        if (!p->panel_rows_dev || !p->pcol_dev || !p->palpha_dev || !p->piece_dev || !p->panel_piece_ptr_dev ||
+            !p->panel_piece_dev)
+            return ADAQP_EINVAL;
+    }
     if (d->schedule != ADAQP_SERIAL) {
         if (!d->event_fork || !d->event_join) return ADAQP_EINVAL;
         if (d->stream_msg == d->stream_agg) return ADAQP_EINVAL;
@@ -186,10 +196,18 @@ int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
     void *ws = overlap_part ? d->workspace_overlap_dev : d->workspace_dependent_dev;
     const int64_t wsb = overlap_part ? d->workspace_overlap_bytes : d->workspace_dependent_bytes;
     const int32_t *tile_off = overlap_part ? d->tile_off_overlap_dev : d->tile_off_dependent_dev;
-    if (tile_off)
-        return adaqp_spmm_csr_tiled(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, d->feat_dev, d->n_feat_rows,
-                                    d->ld, d->dim, d->out_dev, d->ldo, tile_off,
-                                    overlap_part ? d->tile_chunk_overlap : d->tile_chunk_dependent, ws, wsb, st);
+    if (tile_off) {
+        const int rc = adaqp_spmm_csr_tiled(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, d->feat_dev,
+                                            d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, tile_off,
+                                            overlap_part ? d->tile_chunk_overlap : d->tile_chunk_dependent, ws, wsb,
+                                            st);
+        const adaqp_spmm_panels *panels = overlap_part ? &d->panels_overlap : &d->panels_dependent;
+        if (rc != ADAQP_OK || panels->n_panels == 0) return rc;
+        // the rows struck from the tile table, after the tiled launch on the same stream (it zeroes them and
+        // is done with the workspace by then)
+        return adaqp_spmm_csr_panels(panels, rb, re, d->feat_dev, d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo,
+                                     ws, wsb, st);
+    }
     if (!overlap_part && fused_receive(d))
         return adaqp_spmm_csr_packed(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, nz, d->feat_dev,
                                      d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, d->slot_of_row_dev,
@@ -229,6 +247,13 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
         if (part ? d->tile_off_overlap_dev != nullptr : d->tile_off_dependent_dev != nullptr) {
             rc = adaqp_spmm_tiled_workspace_bytes(rows, d->dim, &need);         // that range takes the tiled kernel
             if (rc != ADAQP_OK) return rc;
+            const adaqp_spmm_panels *panels = part ? &d->panels_overlap : &d->panels_dependent;
+            if (panels->n_panels > 0) {
+                int64_t need_panels = 0;
+                rc = adaqp_spmm_panels_workspace_bytes(panels->n_per_tile, d->dim, &need_panels);
+                if (rc != ADAQP_OK) return rc;
+                need = need_panels > need ? need_panels : need;
+            }
         }
         const int64_t have = part ? d->workspace_overlap_bytes : d->workspace_dependent_bytes;
         const void *ws = part ? d->workspace_overlap_dev : d->workspace_dependent_dev;

@@ -89,7 +89,7 @@ def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
 class LayerStep:
     def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False,
                  backward_receive: bool = True, trace: bool = True, fused_receive: bool = False,
-                 tiled: Optional[bool] = None):
+                 tiled: Optional[bool] = None, panels: bool = True, panel_min_row: int = B.SPMM_PANEL_MIN_ROW):
         self.p = p
         self.device = torch.device(device)
         dev = self.device
@@ -133,16 +133,26 @@ class LayerStep:
         # tiled=None lets the library decide per row range (adaqp_spmm_tiled_pays: mean row length).
         self.tile_off_overlap = self.tile_off_dependent = None
         self.tile_chunk_overlap = self.tile_chunk_dependent = 0
+        # within a tiled range, rows with thousands of entries go into dense panels for the matrix cores
+        self.panels_overlap = self.panels_dependent = B.DevicePanels(None)
         ws_o = B.adaqp_spmm_workspace_bytes(oe - ob, self.overlap_nnz, cfg.dim)
         ws_d = B.adaqp_spmm_workspace_bytes(de - db, self.dependent_nnz, cfg.dim)
         if pad and tiled is not False:
             if oe > ob and (tiled or B.adaqp_spmm_tiled_pays(oe - ob, self.overlap_nnz)):
                 bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, ob, oe, p.feat.shape[0])
+                if panels:
+                    self.panels_overlap = B.DevicePanels(B.adaqp_plan_spmm_panels(
+                        p.rowptr, p.col, p.val, ob, oe, p.feat.shape[0], bounds, off, panel_min_row), dev)
+                    ws_o = max(ws_o, B.adaqp_spmm_panels_workspace_bytes(self.panels_overlap.n_per_tile, cfg.dim))
                 self.tile_off_overlap = torch.from_numpy(off).to(dev)
                 self.tile_chunk_overlap = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)
                 ws_o = max(ws_o, B.adaqp_spmm_tiled_workspace_bytes(oe - ob, cfg.dim))
             if de > db and (tiled or B.adaqp_spmm_tiled_pays(de - db, self.dependent_nnz)):
                 bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, db, de, p.feat.shape[0])
+                if panels:
+                    self.panels_dependent = B.DevicePanels(B.adaqp_plan_spmm_panels(
+                        p.rowptr, p.col, p.val, db, de, p.feat.shape[0], bounds, off, panel_min_row), dev)
+                    ws_d = max(ws_d, B.adaqp_spmm_panels_workspace_bytes(self.panels_dependent.n_per_tile, cfg.dim))
                 self.tile_off_dependent = torch.from_numpy(off).to(dev)
                 self.tile_chunk_dependent = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)
                 ws_d = max(ws_d, B.adaqp_spmm_tiled_workspace_bytes(de - db, cfg.dim))
@@ -183,6 +193,10 @@ class LayerStep:
         d.tile_chunk_overlap, d.tile_chunk_dependent = self.tile_chunk_overlap, self.tile_chunk_dependent
         d.tile_off_dependent_dev = None if (self.tile_off_dependent is None or self.fused_receive) \
             else self.tile_off_dependent.data_ptr()
+        if d.tile_off_overlap_dev:
+            d.panels_overlap = self.panels_overlap.c
+        if d.tile_off_dependent_dev:
+            d.panels_dependent = self.panels_dependent.c
         if self.backward and self.backward_receive and pl.seg_order is not None:
             d.recv_seg_order_dev, d.recv_seg_ptr_dev = pl.seg_order.data_ptr(), pl.seg_ptr.data_ptr()
             d.n_recv_seg = pl.seg_ptr.shape[0] - 1

@@ -565,6 +565,135 @@ def test_spmm_tiled_rejects_what_it_cannot_do():
 
 
 # ------------------------------------------------------------------------------------------------------
+# dense panels of the longest rows on the matrix cores, the tiled kernel for the rest
+# ------------------------------------------------------------------------------------------------------
+
+def _gpu_spmm_tiled_and_panels(rowptr, col, val, rb, re, H, dim, ldo, min_row_len, piece_cols, chunk_cols=0):
+    n_cols = H.shape[0]
+    bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, rb, re, n_cols)
+    plan = B.adaqp_plan_spmm_panels(rowptr, col, val, rb, re, n_cols, bounds, off, min_row_len, piece_cols)
+    panels = B.DevicePanels(plan, DEV)
+    out = torch.full((rowptr.shape[0] - 1, ldo), 7.0, dtype=torch.float32, device=DEV)
+    nbytes = max(B.adaqp_spmm_tiled_workspace_bytes(re - rb, dim),
+                 B.adaqp_spmm_panels_workspace_bytes(panels.n_per_tile, dim), 256)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)                                              # NaN patterns: unread unless written first
+    Hd = torch.from_numpy(H).to(DEV)
+    B.adaqp_spmm_csr_tiled(torch.from_numpy(rowptr).to(DEV), torch.from_numpy(col).to(DEV),
+                           torch.from_numpy(val).to(DEV), rb, re, Hd, dim, out, torch.from_numpy(off).to(DEV), ws,
+                           chunk_cols=chunk_cols)
+    ws.fill_(0xFF)
+    B.adaqp_spmm_csr_panels(panels, rb, re, Hd, dim, out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), plan
+
+
+@pytest.mark.parametrize("dim,ld", [(128, 128), (602, 608), (64, 64), (7, 32), (100, 128), (130, 160), (256, 256),
+                                    (1025, 1056)])
+def test_spmm_panels(oracle, dim, ld):
+    _say(f"panel spmm dim={dim} ld={ld}")
+    rng = np.random.default_rng(3000 + dim)
+    n_rows, n_cols = 300, 900
+    degs = rng.integers(0, 90, size=n_rows)
+    heavy = rng.choice(n_rows, size=70, replace=False)                 # two full panels and a part of a third
+    degs[heavy] = rng.integers(100, 600, size=70)
+    degs[heavy[0]] = n_cols                                            # every column
+    degs[heavy[1]] = 100                                               # exactly the threshold
+    rowptr, col, val = _random_graph(rng, n_rows, n_cols, degs)
+    H = np.full((n_cols, ld), np.nan, dtype=np.float32)                # NaN in the row padding
+    H[:, :dim] = rng.standard_normal((n_cols, dim), dtype=np.float32)
+    want, mag = oracle.spmm_csr(rowptr, col, val, 0, n_rows, np.ascontiguousarray(H[:, :dim]), dim)
+    zero_to = _padded_cols(dim, ld)
+    first = None
+    for piece_cols in (8, 64, 1024):
+        got, plan = _gpu_spmm_tiled_and_panels(rowptr, col, val, 0, n_rows, H, dim, ld, 100, piece_cols)
+        assert plan["n_rows_taken"] == int(np.count_nonzero(degs >= 100)) == 70 and plan["n_panels"] == 3
+        err = np.abs(got[:, :dim].astype(np.float64) - want)
+        worst = float((err / (SPMM_RTOL * mag + 1e-30)).max())
+        assert worst <= 1.0, f"piece_cols {piece_cols}: worst error {worst:.3f} x tolerance"
+        assert np.all(got[:, dim:zero_to] == 0.0) and np.all(got[:, zero_to:] == 7.0)
+        if first is None:
+            first = got
+    again, _ = _gpu_spmm_tiled_and_panels(rowptr, col, val, 0, n_rows, H, dim, ld, 100, 8)
+    assert np.array_equal(first.view(np.uint32), again.view(np.uint32)), "runs differ"
+    # a sub-range: rows outside stay untouched, also those that would be long enough
+    sub, plan = _gpu_spmm_tiled_and_panels(rowptr, col, val, 40, 210, H, dim, ld, 100, 64)
+    assert plan["n_rows_taken"] == int(np.count_nonzero(degs[40:210] >= 100))
+    assert np.all(sub[:40] == 7.0) and np.all(sub[210:] == 7.0)
+    err = np.abs(sub[40:210, :dim].astype(np.float64) - want[40:210])
+    assert np.all(err <= SPMM_RTOL * mag[40:210] + 1e-30)
+    # the panels alone write the rows they list and nothing else
+    bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, 0, n_rows, n_cols)
+    plan = B.adaqp_plan_spmm_panels(rowptr, col, val, 0, n_rows, n_cols, bounds, off, 100, 64)
+    panels = B.DevicePanels(plan, DEV)
+    out = torch.full((n_rows, ld), 7.0, dtype=torch.float32, device=DEV)
+    ws = torch.empty(B.adaqp_spmm_panels_workspace_bytes(panels.n_per_tile, dim), dtype=torch.uint8, device=DEV)
+    B.adaqp_spmm_csr_panels(panels, 0, n_rows, torch.from_numpy(H).to(DEV), dim, out, ws)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    listed = np.zeros(n_rows, dtype=bool)
+    listed[plan["panel_rows"][plan["panel_rows"] >= 0]] = True
+    assert np.all(out[~listed] == 7.0)
+    err = np.abs(out[listed, :dim].astype(np.float64) - want[listed])
+    assert np.all(err <= SPMM_RTOL * mag[listed] + 1e-30)
+
+
+def test_spmm_panels_random_shapes(oracle):
+    """Seeded sweep over small shapes: fewer columns than tiles, a single long row, dense blocks, ragged widths."""
+    rng = np.random.default_rng(777)
+    dims = [1, 5, 31, 32, 33, 64, 127, 128, 129, 200, 300, 602]
+    for case in range(20):
+        n_rows = int(rng.choice([1, 2, 31, 32, 33, 65, 150]))
+        n_cols = int(rng.choice([1, 3, 7, 8, 9, 70, 500, 1500]))
+        dim = int(rng.choice(dims))
+        ld = (dim + 31) // 32 * 32
+        kind = case % 4
+        if kind == 0:
+            degs = rng.integers(0, min(n_cols, 300) + 1, size=n_rows)
+        elif kind == 1:
+            degs = np.full(n_rows, n_cols)                              # dense
+        elif kind == 2:
+            degs = rng.integers(0, 3, size=n_rows)
+            degs[rng.integers(0, n_rows)] = n_cols                      # one full row among nearly empty ones
+        else:
+            degs = np.where(rng.random(n_rows) < 0.3, n_cols // 2 + 1, 1)
+        min_len = int(rng.choice([1, 2, 4, 50]))
+        piece_cols = int(rng.choice([8, 16, 256]))
+        _say(f"panel spmm case {case}: rows {n_rows} cols {n_cols} dim {dim} kind {kind} min {min_len} piece {piece_cols}")
+        rowptr, col, val = _random_graph(rng, n_rows, n_cols, degs)
+        if len(col) == 0:
+            continue
+        H = np.full((n_cols, ld), np.nan, dtype=np.float32)
+        H[:, :dim] = rng.standard_normal((n_cols, dim), dtype=np.float32)
+        want, mag = oracle.spmm_csr(rowptr, col, val, 0, n_rows, np.ascontiguousarray(H[:, :dim]), dim)
+        got, plan = _gpu_spmm_tiled_and_panels(rowptr, col, val, 0, n_rows, H, dim, ld, min_len, piece_cols)
+        assert (plan is None) == (not np.any(np.diff(rowptr) >= min_len))
+        err = np.abs(got[:, :dim].astype(np.float64) - want)
+        assert np.all(err <= SPMM_RTOL * mag + 1e-30), f"case {case}"
+        assert np.all(got[:, dim:] == 0.0), f"case {case}: row padding"
+
+
+def test_spmm_panels_rejects_what_it_cannot_do():
+    rng = np.random.default_rng(5)
+    rowptr, col, val = _random_graph(rng, 40, 64, np.full(40, 20))
+    bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, 0, 40, 64)
+    panels = B.DevicePanels(B.adaqp_plan_spmm_panels(rowptr, col, val, 0, 40, 64, bounds, off, 10, 16), DEV)
+    assert panels and panels.c.n_panels == 2
+    need = B.adaqp_spmm_panels_workspace_bytes(panels.n_per_tile, 32)
+    H = torch.zeros((64, 32), dtype=torch.float32, device=DEV)
+    out = torch.zeros((40, 32), dtype=torch.float32, device=DEV)
+    with pytest.raises(B.AdaqpError):                                      # workspace too small
+        B.adaqp_spmm_csr_panels(panels, 0, 40, H, 32, out, torch.empty(need - 256, dtype=torch.uint8, device=DEV))
+    Hbad = torch.zeros((64, 40), dtype=torch.float32, device=DEV)         # pitch not whole lines
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_spmm_csr_panels(panels, 0, 40, Hbad, 32, out, torch.empty(need, dtype=torch.uint8, device=DEV))
+    empty = B.DevicePanels(None)                                           # no panels: a successful no-op
+    B.adaqp_spmm_csr_panels(empty, 0, 40, H, 32, out, torch.empty(256, dtype=torch.uint8, device=DEV))
+    torch.cuda.synchronize()
+    assert torch.all(out == 0)
+
+
+# ------------------------------------------------------------------------------------------------------
 # the layer step
 # ------------------------------------------------------------------------------------------------------
 
@@ -756,6 +885,49 @@ def test_layer_step_with_tiled_aggregation(oracle, name):
         if first is None:
             first = out
         assert np.array_equal(out.view(np.uint32), first.view(np.uint32)), "schedules disagree"
+
+
+@pytest.mark.parametrize("name", ["c0", "c0_backward"])
+def test_layer_step_with_panels(oracle, name):
+    """Tiled aggregation with the longer rows of both ranges in dense panels, every schedule, both directions."""
+    if name == "c0":
+        p = make_partition(CONFIGS["c0"])
+    else:
+        p = make_partition(replace(CONFIGS["c4"], n_local=2000, n_halo=1800, n_send=1500, mean_degree=9.0, dim=128))
+    cfg = p.cfg
+    seed = 8765
+    deg = np.diff(p.rowptr)
+    min_row = max(int(np.quantile(deg[deg > 0], 0.9)), 2)               # the longest tenth of the rows
+    packed_w, params_w, feat_w, out64, mag = _oracle_layer(oracle, p, seed)
+    first = None
+    for schedule in (B.SERIAL, B.ISOLATED, B.FREE):
+        L = LayerStep(p, DEV, seed=seed, tiled=True, backward_receive=False, panel_min_row=min_row)
+        assert L.panels_overlap and L.panels_dependent
+        n_taken = int(np.count_nonzero(L.panels_overlap.tensors["panel_rows"].cpu().numpy() >= 0)) + \
+            int(np.count_nonzero(L.panels_dependent.tensors["panel_rows"].cpu().numpy() >= 0))
+        ob, oe = p.overlap_rows
+        db, de = p.dependent_rows
+        assert n_taken == int(np.count_nonzero(deg[ob:oe] >= min_row)) + int(np.count_nonzero(deg[db:de] >= min_row))
+        if not cfg.backward:
+            L.feat[cfg.n_local: cfg.n_local + cfg.n_send] = float("nan")
+        L.out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        L.run(schedule)
+        L.synchronize()
+        out = L.out.cpu().numpy()
+        assert np.all(np.abs(out.astype(np.float64) - out64) <= SPMM_RTOL * mag + 1e-30), f"schedule {schedule}"
+        if not cfg.backward:
+            assert np.array_equal(L.recv_packed.cpu().numpy()[: L.plan.packed_bytes], packed_w)
+            assert np.array_equal(L.feat.cpu().numpy().view(np.uint32), feat_w.view(np.uint32))
+        if first is None:
+            first = out
+        assert np.array_equal(out.view(np.uint32), first.view(np.uint32)), "schedules disagree"
+    # without panels the same rows come out of the tiled kernel: same sums up to rounding order
+    L = LayerStep(p, DEV, seed=seed, tiled=True, backward_receive=False, panels=False)
+    assert not L.panels_overlap and not L.panels_dependent
+    L.run(B.SERIAL)
+    L.synchronize()
+    assert np.all(np.abs(L.out.cpu().numpy().astype(np.float64) - out64) <= SPMM_RTOL * mag + 1e-30)
 
 
 @pytest.mark.parametrize("schedule_name", ["serial", "isolated"])

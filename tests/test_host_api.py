@@ -180,6 +180,95 @@ def test_plan_spmm_tiles():
         B.adaqp_plan_spmm_tiles(np.array([0, 2], np.int64), np.array([5, 5], np.int32), 0, 1, 8)   # repeated column
 
 
+def _panel_csr(seed, n_rows=90, n_cols=300):
+    rng = np.random.default_rng(seed)
+    rowptr = np.zeros(n_rows + 1, dtype=np.int64)
+    cols = []
+    for r in range(n_rows):
+        d = int(rng.integers(0, 20)) if r % 2 else int(rng.integers(40, 200))           # short and long rows
+        cols.append(np.sort(rng.choice(n_cols, size=d, replace=False)))
+        rowptr[r + 1] = rowptr[r] + d
+    col = np.concatenate(cols).astype(np.int32)
+    val = rng.standard_normal(len(col)).astype(np.float32)
+    val[val == 0] = 1.0
+    return rowptr, col, val
+
+
+def _decode_panels(plan, n_cols):
+    """Dense [n_panels * 32, n_cols] matrix a panel plan stands for, every piece visited once through the
+    per-panel piece lists; also the tile of every piece."""
+    dense = np.zeros((plan["n_panels"] * B.SPMM_PANEL_ROWS, n_cols), dtype=np.float64)
+    npt = plan["n_per_tile"]
+    seen = set()
+    for p in range(plan["n_panels"]):
+        ids = plan["panel_piece"][plan["panel_piece_ptr"][p]: plan["panel_piece_ptr"][p + 1]]
+        assert np.all(np.diff(ids) > 0)                                 # ascending: the summation order
+        for pid in ids:
+            assert pid not in seen
+            seen.add(int(pid))
+            g0, g1 = plan["piece"][pid // npt, pid % npt]
+            assert 0 <= g0 < g1 <= plan["n_groups"]
+            for g in range(g0, g1):
+                for u in range(4):
+                    for h in range(2):
+                        c = plan["pcol"][g, h, u]
+                        dense[p * 32: p * 32 + 32, c] += plan["palpha"][g, 32 * h: 32 * h + 32, u]
+    return dense, seen
+
+
+def test_plan_spmm_panels():
+    n_cols = 300
+    rowptr, col, val = _panel_csr(11, n_cols=n_cols)
+    n_rows = len(rowptr) - 1
+    for (rb, re, min_len, piece_cols) in ((0, n_rows, 40, 16), (7, 61, 100, 8), (0, n_rows, 150, 1024)):
+        bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, rb, re, n_cols)
+        off0 = off.copy()
+        plan = B.adaqp_plan_spmm_panels(rowptr, col, val, rb, re, n_cols, bounds, off, min_len, piece_cols)
+        deg = np.diff(rowptr)
+        want_rows = [r for r in range(rb, re) if deg[r] >= min_len]
+        want_rows.sort(key=lambda r: (-deg[r], r))
+        assert plan["n_rows_taken"] == len(want_rows) and plan["n_panels"] == (len(want_rows) + 31) // 32
+        rows = plan["panel_rows"]
+        assert rows[: len(want_rows)].tolist() == want_rows and np.all(rows[len(want_rows):] == -1)
+        dense, seen = _decode_panels(plan, n_cols)
+        assert len(seen) == plan["n_panel_pieces"]
+        for k, r in enumerate(rows):
+            want = np.zeros(n_cols)
+            if r >= 0:
+                want[col[rowptr[r]: rowptr[r + 1]]] = val[rowptr[r]: rowptr[r + 1]]
+            assert np.array_equal(dense[k], want), (k, r)
+        # pieces of tile t stay inside the tile's column range (the last tile takes the rest), within piece_cols
+        npt = plan["n_per_tile"]
+        used = 0
+        for t in range(B.SPMM_TILES):
+            for i in range(npt):
+                g0, g1 = plan["piece"][t, i]
+                if g0 == g1:
+                    continue
+                used += 1
+                assert (g1 - g0) * 8 <= piece_cols
+                c = plan["pcol"][g0:g1].reshape(-1)
+                assert c.min() >= bounds[t] and (t == B.SPMM_TILES - 1 or c.max() < bounds[t + 1])
+        assert used == plan["n_panel_pieces"]
+        # the rows taken are struck from the tile table, the others are untouched
+        taken = np.zeros(re - rb, dtype=bool)
+        taken[np.array(want_rows, dtype=np.int64) - rb] = True
+        assert np.all(off[taken] == 0) and np.array_equal(off[~taken], off0[~taken])
+    # nothing long enough: no plan, table untouched
+    bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, 0, n_rows, n_cols)
+    off0 = off.copy()
+    assert B.adaqp_plan_spmm_panels(rowptr, col, val, 0, n_rows, n_cols, bounds, off, 1000) is None
+    assert np.array_equal(off, off0)
+    assert B.adaqp_spmm_panels_workspace_bytes(218, 602) == 8 * 218 * 32 * 608 * 4
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_plan_spmm_panels(rowptr, col, val, 0, n_rows, n_cols, bounds, None, 40, 12)     # piece_cols % 8
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_plan_spmm_panels(rowptr, col, val, 0, n_rows, n_cols, bounds, None, 0, 16)      # min_row_len < 1
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_plan_spmm_panels(np.array([0, 2], np.int64), np.array([5, 5], np.int32), np.ones(2, np.float32),
+                                 0, 1, 8, np.zeros(9, np.int32), None, 1, 8)                    # repeated column
+
+
 def test_layer_desc_mirror_matches_the_library():
     import ctypes
     assert int(B.lib().adaqp_layer_desc_bytes()) == ctypes.sizeof(B.LayerDesc)
