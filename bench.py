@@ -8,7 +8,8 @@ the timed region starts.
 
 Prints ONE JSON line.  `value` is whole-step throughput in aggregated edges per second; the codec kernels'
 GB/s and every kernel's fraction of the 8 TB/s HBM peak are in `kernels`; `roofline` describes the dominant
-kernel (the SpMM: tiled over the L2 caches where the rows are long, merge-path otherwise); `cpu_baseline` is the
+kernel (the SpMM: dense panels on the matrix cores for the longest rows and the L2-tiled kernel for the rest where rows
+are long, merge-path otherwise); `cpu_baseline` is the
 CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -25,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 GATHER_RATE_GBPS = 25000.0      # 16-byte-per-lane gather out of L2, every XCD on its own 4 MB: measured on MI355X
+MFMA_FP32_PEAK_TFLOPS = 157.3   # dense fp32 on the matrix cores
 FMA_RATE_PER_S = 78.65e12       # fp32 vector FMAs per second (157.3 TFLOP/s)
 METRIC = "quantize+pack / unpack+dequant GB/s, halo SpMM edges/s, % HBM peak, 1xMI355X"
 
@@ -44,6 +46,8 @@ def parse_args():
                     help="also time 3 steps of the other two schedules (their aggregation launches overlap, which "
                          "inflates per-kernel durations in a trace of the same run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-panels", action="store_true",
+                    help="keep the longest rows in the L2-tiled kernel instead of dense panels on the matrix cores")
     ap.add_argument("--no-tiled", action="store_true",
                     help="aggregate with the merge-path kernel even where the L2-tiled kernel would be chosen")
     ap.add_argument("--calibrate", action="store_true",
@@ -185,7 +189,7 @@ def main():
     p = make_partition(cfg)
     t_gen = time.perf_counter() - t0
     dev = "cuda:0"
-    L = LayerStep(p, dev, seed=2306, tiled=False if args.no_tiled else None)
+    L = LayerStep(p, dev, seed=2306, tiled=False if args.no_tiled else None, panels=not args.no_panels)
     torch.cuda.synchronize()
     sched = {"serial": B.SERIAL, "isolated": B.ISOLATED, "free": B.FREE}
 
@@ -320,6 +324,8 @@ def main():
         if L.tile_off_overlap is not None:
             B.adaqp_spmm_csr_tiled(L.rowptr, L.col, L.val, ob, oe, L.feat, dim, L.out, L.tile_off_overlap,
                                    L.ws_overlap, chunk_cols=L.tile_chunk_overlap, stream=st)
+            if L.panels_overlap:
+                B.adaqp_spmm_csr_panels(L.panels_overlap, ob, oe, L.feat, dim, L.out, L.ws_overlap, stream=st)
         else:
             B.adaqp_spmm_csr(L.rowptr, L.col, L.val, ob, oe, L.feat, dim, L.out, L.ws_overlap,
                              nnz_range=L.overlap_nnz, stream=st)
@@ -328,6 +334,8 @@ def main():
         if L.tile_off_dependent is not None:
             B.adaqp_spmm_csr_tiled(L.rowptr, L.col, L.val, db_, de, L.feat, dim, L.out, L.tile_off_dependent,
                                    L.ws_dependent, chunk_cols=L.tile_chunk_dependent, stream=st)
+            if L.panels_dependent:
+                B.adaqp_spmm_csr_panels(L.panels_dependent, db_, de, L.feat, dim, L.out, L.ws_dependent, stream=st)
         else:
             B.adaqp_spmm_csr(L.rowptr, L.col, L.val, db_, de, L.feat, dim, L.out, L.ws_dependent,
                              nnz_range=L.dependent_nnz, stream=st)
@@ -349,17 +357,44 @@ def main():
                          "GBps": b_o / t_o / 1e6, "frac_hbm": b_o / t_o / 1e6 / HBM_PEAK_GBPS}
     kernels[names[1]] = {"ms": t_d, "edges": L.dependent_nnz, "edges_per_s": L.dependent_nnz / t_d * 1e3,
                          "GBps": b_d / t_d / 1e6, "frac_hbm": b_d / t_d / 1e6 / HBM_PEAK_GBPS}
+    # where panels take the longest rows: the two kernels of each range on their own
+    deg = np.diff(p.rowptr)
+    panel_parts = {}
+    for tag, pan, rb, re, ws, off_dev, chunk in (
+            (names[0], L.panels_overlap, ob, oe, L.ws_overlap, L.tile_off_overlap, L.tile_chunk_overlap),
+            (names[1], L.panels_dependent, db_, de, L.ws_dependent, L.tile_off_dependent, L.tile_chunk_dependent)):
+        if not pan:
+            continue
+        rows_p = pan.tensors["panel_rows"].cpu().numpy()
+        rows_p = rows_p[rows_p >= 0]
+        t_p = event_time_ms(st, lambda i: B.adaqp_spmm_csr_panels(pan, rb, re, L.feat, dim, L.out, ws, stream=st), sreps)
+        t_t = event_time_ms(st, lambda i: B.adaqp_spmm_csr_tiled(L.rowptr, L.col, L.val, rb, re, L.feat, dim, L.out,
+                                                                 off_dev, ws, chunk_cols=chunk, stream=st), sreps)
+        n_chunks = (dim + 127) // 128
+        panel_parts[tag] = {"panel_rows": int(rows_p.size), "panel_edges": int(deg[rows_p].sum()),
+                            "panels": int(pan.c.n_panels), "panel_columns_padded": int(pan.c.n_groups) * 8,
+                            "ms_panels": t_p, "ms_tiled_other_rows": t_t,
+                            "mfma_flops_executed": 2.0 * 32 * int(pan.c.n_groups) * 8 * n_chunks * 128}
+        kernels[tag]["panels"] = panel_parts[tag]
     # the whole row range in one launch (what a step without the central / marginal split would run)
     all_rows = p.n_rows
     if tiled_both:
         bounds_all, off_all = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, 0, all_rows, p.feat.shape[0])
+        panels_all = B.DevicePanels(None)
+        if not args.no_panels:
+            panels_all = B.DevicePanels(B.adaqp_plan_spmm_panels(p.rowptr, p.col, p.val, 0, all_rows,
+                                                                 p.feat.shape[0], bounds_all, off_all), dev)
         off_all_dev = torch.from_numpy(off_all).to(dev)
         chunk_all = B.adaqp_spmm_tiled_chunk_cols(bounds_all, dim)
-        ws_all = torch.empty(B.adaqp_spmm_tiled_workspace_bytes(all_rows, dim), dtype=torch.uint8, device=dev)
+        ws_all = torch.empty(max(B.adaqp_spmm_tiled_workspace_bytes(all_rows, dim),
+                                 B.adaqp_spmm_panels_workspace_bytes(panels_all.n_per_tile, dim)),
+                             dtype=torch.uint8, device=dev)
 
         def spmm_all(i):
             B.adaqp_spmm_csr_tiled(L.rowptr, L.col, L.val, 0, all_rows, L.feat, dim, L.out, off_all_dev, ws_all,
                                    chunk_cols=chunk_all, stream=st)
+            if panels_all:
+                B.adaqp_spmm_csr_panels(panels_all, 0, all_rows, L.feat, dim, L.out, ws_all, stream=st)
     else:
         ws_all = torch.empty(max(B.adaqp_spmm_workspace_bytes(all_rows, p.nnz, dim), 256), dtype=torch.uint8,
                              device=dev)
@@ -369,7 +404,8 @@ def main():
                              stream=st)
     t_all = event_time_ms(st, spmm_all, sreps)
     kernels["spmm_all_rows_one_launch"] = {"ms": t_all, "edges": p.nnz, "edges_per_s": p.nnz / t_all * 1e3,
-                                           "kernel": "tiled" if tiled_both else "merge-path"}
+                                           "kernel": ("tiled + panels" if panel_parts else "tiled") if tiled_both
+                                           else "merge-path"}
     del ws_all
     # dominant kernel: the merge-path SpMM, two launches per step; per-launch averages
     achieved = (b_o + b_d) / (t_o + t_d) / 1e6
@@ -392,19 +428,56 @@ def main():
                 "frac_hbm_compulsory": compulsory / t_both / 1e6 / HBM_PEAK_GBPS,
                 "gather_rate_GBps": GATHER_RATE_GBPS, "fma_rate_per_s": FMA_RATE_PER_S,
                 "t_ceiling_ms": t_ceiling, "t_ceiling_over_t": t_ceiling / t_both}
+    launches, avg_launch_ms, alg_bytes = 2, (t_o + t_d) / 2, (b_o + b_d) / 2
+    mfma = None
+    if panel_parts:
+        # most of the step's time is now in the panel kernel: one launch per row range that has panels
+        spmm_kernel = "spmm_panel_kernel"
+        t_p = sum(v["ms_panels"] for v in panel_parts.values())
+        b_p = sum(spmm_bytes(v["panel_edges"], v["panel_rows"], dim) for v in panel_parts.values())
+        launches = len(panel_parts)
+        achieved, avg_launch_ms, alg_bytes = b_p / t_p / 1e6, t_p / launches, b_p / launches
+        executed = sum(v["mfma_flops_executed"] for v in panel_parts.values())
+        useful = sum(2.0 * v["panel_edges"] * dim for v in panel_parts.values())
+        mfma = {"peak_TFLOPs_fp32": MFMA_FP32_PEAK_TFLOPS, "TFLOPs_executed": executed / t_p / 1e9,
+                "frac_executed": executed / t_p / 1e9 / MFMA_FP32_PEAK_TFLOPS,
+                "TFLOPs_useful": useful / t_p / 1e9, "frac_useful": useful / t_p / 1e9 / MFMA_FP32_PEAK_TFLOPS,
+                "panel_density": sum(v["panel_edges"] for v in panel_parts.values())
+                / (32.0 * sum(v["panel_columns_padded"] for v in panel_parts.values())),
+                "note": "executed counts the zeros of the dense panels and the padding of dim to 128-column chunks"}
+    if panel_parts:
+        # the entry-by-entry ceiling above does not bind the panel kernel (one fetch serves up to 32 entries):
+        # what the step fetches now is one row of H per panel column plus one per entry of the other rows
+        fetched = sum(v["panel_columns_padded"] for v in panel_parts.values()) + \
+            p.nnz - sum(v["panel_edges"] for v in panel_parts.values())
+        executed = sum(v["mfma_flops_executed"] for v in panel_parts.values())
+        ceilings["with_panels"] = {
+            "neighbour_rows_fetched": fetched, "t_gather_ms": fetched * 4 * dim / GATHER_RATE_GBPS / 1e6,
+            "t_mfma_executed_ms": executed / MFMA_FP32_PEAK_TFLOPS / 1e9,
+            "note": "floors of the panel + tiled pair: its gather at the L2 rate, its matrix-core work at the "
+                    "fp32 MFMA peak; the two overlap at best"}
     roofline = {"kernel": spmm_kernel, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                "launches_per_step": 2, "avg_launch_ms": (t_o + t_d) / 2,
-                "algorithmic_bytes_per_launch": (b_o + b_d) / 2,
+                "launches_per_step": launches, "avg_launch_ms": avg_launch_ms,
+                "algorithmic_bytes_per_launch": alg_bytes,
+                "whole_aggregation": {"GBps": (b_o + b_d) / t_both / 1e6, "ms": t_both,
+                                      "frac": (b_o + b_d) / t_both / 1e6 / HBM_PEAK_GBPS},
                 "ceilings": ceilings,
-                "binding_limit": ("gather rate of the CUs' vector-memory pipeline out of L2 (22-25 TB/s measured), "
+                "binding_limit": ("the fp32 matrix cores and the gather that feeds them: each neighbour row is "
+                                  "fetched once per 32-row panel (out of the XCD's L2) and multiplied with the panel's "
+                                  "dense coefficient table" if panel_parts else
+                                  "gather rate of the CUs' vector-memory pipeline out of L2 (22-25 TB/s measured), "
                                   "not HBM: most neighbour rows hit in the XCD's L2" if tiled else
                                   "the path behind L2 (fabric / Infinity Cache / HBM, about 7.5 TB/s measured) "
                                   "for the rows that miss L2"),
                 "note": "algorithmic bytes count one neighbour row per edge; rows re-used out of L2 / Infinity "
                         "Cache make the fraction exceed what HBM alone could deliver"
-                        + ("; the tiled kernel is built for exactly that re-use (one column range of the graph "
+                        + ("; the panel kernel fetches a neighbour row once for up to 32 edges, its piece-sum "
+                           "kernel is included in the launch time" if panel_parts else
+                           "; the tiled kernel is built for exactly that re-use (one column range of the graph "
                            "per XCD), its partial-sum reduction kernel is included in the launch time" if tiled else "")}
+    if mfma:
+        roofline["mfma"] = mfma
 
     result = {
         "metric": METRIC, "value": p.nnz / ms_per_step * 1e3, "unit": "edges/s",

@@ -290,7 +290,9 @@ int adaqp_spmm_csr_tiled(const int64_t *rowptr_dev, const int32_t *col_dev, cons
  * A zero coefficient times a non-finite H entry is NaN: H must be finite (as everywhere in this library), or a
  * non-finite row of H reaches all rows of the panels that list its column. */
 #define ADAQP_SPMM_PANEL_ROWS 32
-#define ADAQP_SPMM_PANEL_MIN_ROW 2048     /* default: rows with at least this many entries go into panels */
+#define ADAQP_SPMM_PANEL_MIN_ROW 6144     /* default: rows with at least this many entries go into panels (about a
+                                             tenth of the columns such rows reference in the Reddit-shaped workload:
+                                             panels sparser than that lose against the tiled kernel) */
 #define ADAQP_SPMM_PANEL_PIECE_COLS 1024  /* default: panel columns per piece of work (a multiple of 8) */
 
 /* Device side of a panel plan for one row range.  All arrays are device copies of what adaqp_plan_spmm_panels
@@ -314,7 +316,7 @@ typedef struct adaqp_spmm_panels {
  * range (the pieces of a panel follow the same eight column ranges, so that each L2 keeps seeing one range).
  * Rows are taken in order of descending length (ties: ascending row), 32 per panel; the last panel may be
  * partly filled.  Every (panel, tile) column list is padded to a multiple of 8 with coefficient 0 and cut
- * into pieces of piece_cols columns.
+ * into pieces of piece_cols columns; a tile's pieces are listed in order of their first column.
  * Call twice: first with panel_rows_out NULL, which only fills sizes_out[5] = { rows taken, n_panels,
  * n_groups, n_per_tile, n_panel_pieces }; then with arrays of those sizes (layouts as in adaqp_spmm_panels).
  * tile_off_inout (may be NULL): adaqp_plan_spmm_tiles' table for the range; on the filling call the rows taken

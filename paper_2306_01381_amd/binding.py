@@ -278,7 +278,7 @@ def adaqp_spmm_csr(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, r
 SPMM_TILES = 8
 SPMM_TILED_SHORT_ROW = 64
 SPMM_PANEL_ROWS = 32
-SPMM_PANEL_MIN_ROW = 2048
+SPMM_PANEL_MIN_ROW = 6144
 SPMM_PANEL_PIECE_COLS = 1024
 
 

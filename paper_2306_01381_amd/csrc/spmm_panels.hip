@@ -211,7 +211,7 @@ extern "C" int adaqp_plan_spmm_panels(const int64_t *rowptr_host, const int32_t 
         std::memset(palpha_out, 0, (size_t)sizes_out[2] * kWave * 4 * sizeof(float));
     }
     struct Piece {
-        int32_t panel, g0, g1;
+        int32_t panel, g0, g1, first_col;
     };
     std::vector<Piece> lists[kTiles];
     std::vector<uint8_t> used((size_t)n_cols, 0);
@@ -261,7 +261,8 @@ extern "C" int adaqp_plan_spmm_panels(const int64_t *rowptr_host, const int32_t 
                 }
                 for (int64_t s0 = 0; s0 < ng; s0 += piece_groups)
                     lists[t].push_back(Piece{(int32_t)p, (int32_t)(n_groups + s0),
-                                             (int32_t)(n_groups + std::min<int64_t>(s0 + piece_groups, ng))});
+                                             (int32_t)(n_groups + std::min<int64_t>(s0 + piece_groups, ng)),
+                                             distinct[at + (size_t)(s0 * 8)]});
                 n_groups += ng;
             }
             at = end;
@@ -278,6 +279,11 @@ extern "C" int adaqp_plan_spmm_panels(const int64_t *rowptr_host, const int32_t 
             }
         }
     }
+    // within a tile, pieces in order of their first column: the pieces of different panels that walk the same
+    // rows of H are launched next to each other (a few percent faster than panel by panel)
+    for (int t = 0; t < kTiles; ++t)
+        std::stable_sort(lists[t].begin(), lists[t].end(),
+                         [](const Piece &x, const Piece &y) { return x.first_col < y.first_col; });
     size_t n_per_tile = 0, n_pieces = 0;
     for (int t = 0; t < kTiles; ++t) {
         n_per_tile = std::max(n_per_tile, lists[t].size());

@@ -89,7 +89,8 @@ def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
 class LayerStep:
     def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False,
                  backward_receive: bool = True, trace: bool = True, fused_receive: bool = False,
-                 tiled: Optional[bool] = None, panels: bool = True, panel_min_row: int = B.SPMM_PANEL_MIN_ROW):
+                 tiled: Optional[bool] = None, panels: bool = True, panel_min_row: int = B.SPMM_PANEL_MIN_ROW,
+                 panel_piece_cols: int = B.SPMM_PANEL_PIECE_COLS):
         self.p = p
         self.device = torch.device(device)
         dev = self.device
@@ -142,7 +143,7 @@ class LayerStep:
                 bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, ob, oe, p.feat.shape[0])
                 if panels:
                     self.panels_overlap = B.DevicePanels(B.adaqp_plan_spmm_panels(
-                        p.rowptr, p.col, p.val, ob, oe, p.feat.shape[0], bounds, off, panel_min_row), dev)
+                        p.rowptr, p.col, p.val, ob, oe, p.feat.shape[0], bounds, off, panel_min_row, panel_piece_cols), dev)
                     ws_o = max(ws_o, B.adaqp_spmm_panels_workspace_bytes(self.panels_overlap.n_per_tile, cfg.dim))
                 self.tile_off_overlap = torch.from_numpy(off).to(dev)
                 self.tile_chunk_overlap = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)
@@ -151,7 +152,7 @@ class LayerStep:
                 bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, db, de, p.feat.shape[0])
                 if panels:
                     self.panels_dependent = B.DevicePanels(B.adaqp_plan_spmm_panels(
-                        p.rowptr, p.col, p.val, db, de, p.feat.shape[0], bounds, off, panel_min_row), dev)
+                        p.rowptr, p.col, p.val, db, de, p.feat.shape[0], bounds, off, panel_min_row, panel_piece_cols), dev)
                     ws_d = max(ws_d, B.adaqp_spmm_panels_workspace_bytes(self.panels_dependent.n_per_tile, cfg.dim))
                 self.tile_off_dependent = torch.from_numpy(off).to(dev)
                 self.tile_chunk_dependent = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)

@@ -43,6 +43,13 @@ def _sample_rows(rng, rowptr, lo, hi, k):
     picks = set((lo + rng.integers(0, hi - lo, size=k)).tolist()) | {lo, hi - 1}
     picks |= set((lo + np.argsort(deg)[-4:]).tolist())        # the longest rows (split over many pieces)
     picks |= set((lo + np.argsort(deg)[:2]).tolist())         # the shortest
+    # rows on both sides of the length from which a row is aggregated in a dense panel, and a few inside panels
+    order = np.argsort(-deg, kind="stable")
+    n_long = int(np.count_nonzero(deg >= B.SPMM_PANEL_MIN_ROW))
+    if n_long:
+        picks |= set((lo + order[max(n_long - 3, 0): n_long + 3]).tolist())
+        picks |= set((lo + order[rng.integers(0, n_long, size=6)]).tolist())
+        picks |= set((lo + order[[31, 32, 33]][: max(min(n_long - 31, 3), 0)]).tolist())     # around a panel seam
     return sorted(picks)
 
 
