@@ -12,13 +12,13 @@
  *   aggregation   out_v = sum over u in {v} U N(v) of alpha(u,v) * h_u as a CSR SpMM, central rows on a
  *                 second stream so that they overlap the message path      (Sec. 2.1 Eq. 3, Sec. 3.4 Fig. 7)
  *                 - optionally straight from the packed receive buffer, or tiled over the GPU's eight L2
- *                 caches for graphs with long rows
+ *                 caches for graphs with long rows, the longest of them as dense panels on the matrix cores
  *   assignment    the next period's bit-widths from the traced beta values (host code)     (Sec. 4.2 Eq. 7-9)
  *
  * Conventions
  *   - "dev" pointers are device pointers valid on the current HIP device, "host" pointers are host memory.
- *   - Every buffer is owned by the caller.  The library allocates and frees nothing; scratch memory is
- *     passed in as a workspace.
+ *   - Every buffer is owned by the caller.  The library allocates and frees no device memory; scratch memory
+ *     is passed in as a workspace.  (The host-only planning calls use temporary host memory.)
  *   - Calls that take a stream only enqueue work on it and return; they never synchronise.
  *     `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   - Return value: ADAQP_OK (0) or a negative adaqp_status.  Argument errors are detected on the host
