@@ -37,10 +37,13 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c1", help="c0..c4 (c1 is the configuration the metric is quoted on)")
-    ap.add_argument("--schedule", default="serial", choices=["serial", "isolated", "free"],
-                    help="schedule of the timed steps.  The three give the same time on one GPU (the aggregation "
-                         "fills the device, and there is no transfer to hide); serial is the default because its "
-                         "kernels never overlap, so per-kernel durations of a rocprofv3 trace are meaningful")
+    ap.add_argument("--schedule", default="isolated", choices=["serial", "isolated", "free"],
+                    help="schedule of the timed steps.  isolated (the default) is the paper's Fig. 7: the central rows "
+                         "start on the second stream once quantisation is done.  Where the aggregation is one kernel "
+                         "per row range the three take the same time on one GPU (the aggregation fills the device "
+                         "and there is no transfer to hide); where the longest rows go through the panel kernel the "
+                         "two-stream schedules run a panel kernel beside a tiled one and are faster than serial.  The "
+                         "per-kernel figures under `kernels` are always timed one launch at a time")
     ap.add_argument("--kernel-reps", type=int, default=20, help="launches per kernel in the breakdown")
     ap.add_argument("--all-schedules", action="store_true",
                     help="also time 3 steps of the other two schedules (their aggregation launches overlap, which "

@@ -268,7 +268,8 @@ int adaqp_spmm_tiled_workspace_bytes(int64_t n_rows, int32_t dim, int64_t *bytes
 /* out[r, 0:dim] = sum_j val[j] * H[col[j], 0:dim] for r in [row_begin, row_end), like adaqp_spmm_csr.
  * tile_off_dev: device copy of adaqp_plan_spmm_tiles' table for the same row range (planning rejects graphs
  * with out-of-range columns; should the device arrays hold one nevertheless, it is read as column 0 with
- * coefficient 0).  A table that disagrees with rowptr is clamped to the row (wrong sums, no stray access).  The summation order is fixed by the table and the launch geometry: runs are bit-identical.
+ * coefficient 0).  A row whose table entries are negative (struck by adaqp_plan_spmm_panels) is skipped: its
+ * row of out is not written.  A table that disagrees with rowptr is clamped to the row (wrong sums, no stray access).  The summation order is fixed by the table and the launch geometry: runs are bit-identical.
  * H and out must be line-padded (pitch a multiple of 32 floats, base 128-byte aligned); the padding of the
  * written rows is set to zero.  chunk_cols: 64, 128 or 0 (= 128), see adaqp_spmm_tiled_chunk_cols; the result's
  * bits depend on it.  workspace_dev: 256-byte aligned, >= adaqp_spmm_tiled_workspace_bytes.
@@ -285,8 +286,10 @@ int adaqp_spmm_csr_tiled(const int64_t *rowptr_dev, const int32_t *col_dev, cons
  * the distinct columns its rows reference and a dense [columns][32] table of coefficients alpha(u, v) (0 where a
  * row lacks the column).  The same sum of Sec. 2.1 Eq. 3 is then a small dense product per panel: each row of H
  * is fetched once per panel instead of once per entry, and the multiply-adds run on the fp32 matrix cores.
- * The rows taken into panels are struck from the tile table, so adaqp_spmm_csr_tiled covers the remaining rows
- * and adaqp_spmm_csr_panels these; call the tiled one first (it writes zeros to the struck rows).
+ * The rows taken into panels are struck from the tile table (all entries -1), so adaqp_spmm_csr_tiled covers the
+ * remaining rows and adaqp_spmm_csr_panels these.  The two calls write disjoint rows of out: with a workspace
+ * each they may run in either order or at the same time on two streams (they suit each other: one keeps the
+ * matrix cores busy, the other the vector-memory pipeline).
  * A zero coefficient times a non-finite H entry is NaN: H must be finite (as everywhere in this library), or a
  * non-finite row of H reaches all rows of the panels that list its column. */
 #define ADAQP_SPMM_PANEL_ROWS 32
@@ -319,8 +322,8 @@ typedef struct adaqp_spmm_panels {
  * into pieces of piece_cols columns; a tile's pieces are listed in order of their first column.
  * Call twice: first with panel_rows_out NULL, which only fills sizes_out[5] = { rows taken, n_panels,
  * n_groups, n_per_tile, n_panel_pieces }; then with arrays of those sizes (layouts as in adaqp_spmm_panels).
- * tile_off_inout (may be NULL): adaqp_plan_spmm_tiles' table for the range; on the filling call the rows taken
- * get all-zero entries, i.e. adaqp_spmm_csr_tiled skips them.
+ * tile_off_inout (may be NULL): adaqp_plan_spmm_tiles' table for the range; on the filling call all entries of
+ * the rows taken become -1, i.e. adaqp_spmm_csr_tiled neither aggregates nor writes them.
  * Errors: EINVAL (bad CSR, min_row_len < 1, piece_cols not a positive multiple of 8), ESIZE (sizes beyond
  * 2^31 - 1). */
 int adaqp_plan_spmm_panels(const int64_t *rowptr_host, const int32_t *col_host, const float *val_host,
@@ -403,7 +406,13 @@ typedef struct adaqp_layer_desc {
     int32_t tile_chunk_overlap, tile_chunk_dependent;   /* chunk_cols of the two tiled launches (0 = 128) */
     adaqp_spmm_panels panels_overlap;       /* optional (n_panels = 0: none): adaqp_plan_spmm_panels of the two row */
     adaqp_spmm_panels panels_dependent;     /* ranges; only with that range's tile table.  The range's workspace must
-                                               hold adaqp_spmm_panels_workspace_bytes as well */
+                                               then hold adaqp_spmm_tiled_workspace_bytes PLUS
+                                               adaqp_spmm_panels_workspace_bytes (the panel part starts where the
+                                               tiled part ends).  Forward step, both ranges tiled, schedule ISOLATED
+                                               or FREE: the panel launches go to stream_msg (after the
+                                               de-quantisation) and both tiled launches to stream_agg, so that a
+                                               panel kernel and a tiled kernel run side by side; otherwise a
+                                               range's panels follow its tiled launch on the same stream */
     const int32_t *recv_seg_order_dev;  /* backward only, optional: adaqp_plan_recv_segments of halo_idx */
     const int64_t *recv_seg_ptr_dev;
     int64_t n_recv_seg;

@@ -188,7 +188,18 @@ bool fused_receive(const adaqp_layer_desc *d)
            d->packed_bytes >= 4;
 }
 
-int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
+// Workspace of a row range: the tiled kernel's partial sums first, then (if the range has panels) the panel
+// kernel's piece sums, so that the two kernels can run at the same time.
+int64_t tiled_part_bytes(const adaqp_layer_desc *d, bool overlap_part)
+{
+    const int64_t rows = overlap_part ? d->overlap_end - d->overlap_begin : d->dependent_end - d->dependent_begin;
+    int64_t bytes = 0;
+    if (adaqp_spmm_tiled_workspace_bytes(rows, d->dim, &bytes) != ADAQP_OK) return -1;
+    return bytes;
+}
+
+// The rows of a range that are aggregated entry by entry: all of them, or those outside the panels.
+int aggregate_rows(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
 {
     const int64_t rb = overlap_part ? d->overlap_begin : d->dependent_begin;
     const int64_t re = overlap_part ? d->overlap_end : d->dependent_end;
@@ -196,18 +207,10 @@ int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
     void *ws = overlap_part ? d->workspace_overlap_dev : d->workspace_dependent_dev;
     const int64_t wsb = overlap_part ? d->workspace_overlap_bytes : d->workspace_dependent_bytes;
     const int32_t *tile_off = overlap_part ? d->tile_off_overlap_dev : d->tile_off_dependent_dev;
-    if (tile_off) {
-        const int rc = adaqp_spmm_csr_tiled(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, d->feat_dev,
-                                            d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, tile_off,
-                                            overlap_part ? d->tile_chunk_overlap : d->tile_chunk_dependent, ws, wsb,
-                                            st);
-        const adaqp_spmm_panels *panels = overlap_part ? &d->panels_overlap : &d->panels_dependent;
-        if (rc != ADAQP_OK || panels->n_panels == 0) return rc;
-        // the rows struck from the tile table, after the tiled launch on the same stream (it zeroes them and
-        // is done with the workspace by then)
-        return adaqp_spmm_csr_panels(panels, rb, re, d->feat_dev, d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo,
-                                     ws, wsb, st);
-    }
+    if (tile_off)
+        return adaqp_spmm_csr_tiled(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, d->feat_dev,
+                                    d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, tile_off,
+                                    overlap_part ? d->tile_chunk_overlap : d->tile_chunk_dependent, ws, wsb, st);
     if (!overlap_part && fused_receive(d))
         return adaqp_spmm_csr_packed(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, nz, d->feat_dev,
                                      d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, d->slot_of_row_dev,
@@ -215,6 +218,33 @@ int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
                                      d->row_offset_dev, d->n_send, ws, wsb, st);
     return adaqp_spmm_csr(d->rowptr_dev, d->col_dev, d->val_dev, d->nnz, rb, re, nz, d->feat_dev,
                           d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, ws, wsb, st);
+}
+
+bool has_panels(const adaqp_layer_desc *d, bool overlap_part)
+{
+    const int32_t *tile_off = overlap_part ? d->tile_off_overlap_dev : d->tile_off_dependent_dev;
+    return tile_off && (overlap_part ? d->panels_overlap.n_panels : d->panels_dependent.n_panels) > 0;
+}
+
+// The rows of a range that were struck from its tile table.  Own part of the workspace, disjoint output rows:
+// independent of aggregate_rows of the same range.
+int aggregate_panels(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
+{
+    if (!has_panels(d, overlap_part)) return ADAQP_OK;
+    const int64_t rb = overlap_part ? d->overlap_begin : d->dependent_begin;
+    const int64_t re = overlap_part ? d->overlap_end : d->dependent_end;
+    char *ws = static_cast<char *>(overlap_part ? d->workspace_overlap_dev : d->workspace_dependent_dev);
+    const int64_t wsb = overlap_part ? d->workspace_overlap_bytes : d->workspace_dependent_bytes;
+    const int64_t skip = tiled_part_bytes(d, overlap_part);
+    if (skip < 0 || !ws || wsb < skip) return ADAQP_ESIZE;
+    return adaqp_spmm_csr_panels(overlap_part ? &d->panels_overlap : &d->panels_dependent, rb, re, d->feat_dev,
+                                 d->n_feat_rows, d->ld, d->dim, d->out_dev, d->ldo, ws + skip, wsb - skip, st);
+}
+
+int aggregate(const adaqp_layer_desc *d, bool overlap_part, hipStream_t st)
+{
+    const int rc = aggregate_rows(d, overlap_part, st);
+    return rc != ADAQP_OK ? rc : aggregate_panels(d, overlap_part, st);
 }
 
 int loop_back(const adaqp_layer_desc *d, hipStream_t st)
@@ -252,7 +282,7 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
                 int64_t need_panels = 0;
                 rc = adaqp_spmm_panels_workspace_bytes(panels->n_per_tile, d->dim, &need_panels);
                 if (rc != ADAQP_OK) return rc;
-                need = need_panels > need ? need_panels : need;
+                need += need_panels;                        // side by side: the two kernels may run together
             }
         }
         const int64_t have = part ? d->workspace_overlap_bytes : d->workspace_dependent_bytes;
@@ -265,6 +295,8 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
     hipEvent_t fork = (hipEvent_t)d->event_fork, join = (hipEvent_t)d->event_join;
     const bool forward = d->direction == ADAQP_FORWARD;
     const bool both_tiled = d->tile_off_overlap_dev && d->tile_off_dependent_dev;
+    const bool paired = forward && both_tiled && d->schedule != ADAQP_SERIAL &&
+                        (has_panels(d, true) || has_panels(d, false));
     bool forked = false;
     auto fork_now = [&]() -> int {
         if (d->schedule == ADAQP_SERIAL) return ADAQP_OK;
@@ -280,6 +312,12 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
         forked = false;
         return ADAQP_OK;
     };
+    auto agg_waits_for_msg = [&]() -> int {
+        // the fork event is free again: its first wait has been enqueued, and a wait refers to the record before it
+        ADAQP_HIP_TRY(hipEventRecord(fork, msg));
+        ADAQP_HIP_TRY(hipStreamWaitEvent(agg, fork, 0));
+        return ADAQP_OK;
+    };
 #define ADAQP_STEP(expr)                    \
     do {                                    \
         rc = (expr);                        \
@@ -290,14 +328,14 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
         // FREE: the central rows start right away.  ISOLATED: they start once quantisation is done.
         if (d->schedule == ADAQP_FREE) {
             ADAQP_STEP(fork_now());
-            ADAQP_STEP(aggregate(d, true, agg));
+            ADAQP_STEP(paired ? aggregate_rows(d, true, agg) : aggregate(d, true, agg));
         }
         ADAQP_STEP(adaqp_quantize_pack_trace(d->feat_dev, d->n_feat_rows, d->ld, d->dim, d->send_idx_dev,
                                              d->bits_dev, d->row_offset_dev, d->n_send, d->seed, d->packed_dev,
                                              d->packed_bytes, d->params_dev, d->alpha_sq_dev, d->beta_dev, msg));
         if (d->schedule == ADAQP_ISOLATED) {
             ADAQP_STEP(fork_now());
-            ADAQP_STEP(aggregate(d, true, agg));
+            ADAQP_STEP(paired ? aggregate_rows(d, true, agg) : aggregate(d, true, agg));
         }
         ADAQP_STEP(loop_back(d, msg));
         if (!fused_receive(d))
@@ -305,10 +343,19 @@ extern "C" int adaqp_layer_step(const adaqp_layer_desc *d)
                                             d->row_offset_dev, d->halo_idx_dev, d->recv_order_dev, d->n_send, d->dim,
                                             d->feat_dev, d->n_feat_rows, d->ld, msg));
         if (d->schedule == ADAQP_SERIAL) ADAQP_STEP(aggregate(d, true, msg));
-        // two tiled aggregations side by side would bring two column ranges to every L2 and lose what the
-        // tiling is for: the dependent one waits for the other (which has overlapped the message path by now)
-        if (both_tiled) ADAQP_STEP(join_now());
-        ADAQP_STEP(aggregate(d, false, msg));
+        if (paired) {
+            // a panel kernel (matrix cores) and a tiled kernel (vector-memory pipeline) fill each other's gaps:
+            // both tiled launches on the second stream, one after the other, both panel launches here
+            ADAQP_STEP(agg_waits_for_msg());                            // the halo rows are in place
+            ADAQP_STEP(aggregate_panels(d, true, msg));
+            ADAQP_STEP(aggregate_rows(d, false, agg));
+            ADAQP_STEP(aggregate_panels(d, false, msg));
+        } else {
+            // two tiled aggregations side by side would bring two column ranges to every L2 and lose what the
+            // tiling is for: the dependent one waits for the other (which has overlapped the message path by now)
+            if (both_tiled) ADAQP_STEP(join_now());
+            ADAQP_STEP(aggregate(d, false, msg));
+        }
     } else {
         // backward: the rows that are sent are aggregated first, the local rows overlap their quantisation
         // (FREE) or only their transfer (ISOLATED)

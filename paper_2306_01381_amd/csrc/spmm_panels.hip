@@ -319,7 +319,7 @@ extern "C" int adaqp_plan_spmm_panels(const int64_t *rowptr_host, const int32_t 
             panel_piece_out[next[(size_t)lists[t][i].panel]++] = (int32_t)((size_t)t * n_per_tile + i);
     if (tile_off_inout)
         for (int64_t k = 0; k < n_heavy; ++k)
-            std::fill_n(tile_off_inout + (heavy[(size_t)k] - row_begin) * (kTiles + 1), kTiles + 1, 0);
+            std::fill_n(tile_off_inout + (heavy[(size_t)k] - row_begin) * (kTiles + 1), kTiles + 1, -1);
     return ADAQP_OK;
 }
 

@@ -259,6 +259,7 @@ __global__ __launch_bounds__(kBlock) void spmm_tiled_reduce_kernel(const TiledAr
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t r = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     if (r >= a.n_rows) return;
+    if (a.tile_off[r * (kTiles + 1)] < 0) return;           // a row struck from the table: someone else's to write
     uint32_t present = 0;
     for (int t = 0; t < kTiles; ++t) {
         int64_t first;

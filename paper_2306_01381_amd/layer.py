@@ -144,19 +144,20 @@ class LayerStep:
                 if panels:
                     self.panels_overlap = B.DevicePanels(B.adaqp_plan_spmm_panels(
                         p.rowptr, p.col, p.val, ob, oe, p.feat.shape[0], bounds, off, panel_min_row, panel_piece_cols), dev)
-                    ws_o = max(ws_o, B.adaqp_spmm_panels_workspace_bytes(self.panels_overlap.n_per_tile, cfg.dim))
                 self.tile_off_overlap = torch.from_numpy(off).to(dev)
                 self.tile_chunk_overlap = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)
-                ws_o = max(ws_o, B.adaqp_spmm_tiled_workspace_bytes(oe - ob, cfg.dim))
+                # partial sums of the tiled kernel, then the piece sums of the panel kernel (they may run together)
+                ws_o = max(ws_o, B.adaqp_spmm_tiled_workspace_bytes(oe - ob, cfg.dim)
+                           + B.adaqp_spmm_panels_workspace_bytes(self.panels_overlap.n_per_tile, cfg.dim))
             if de > db and (tiled or B.adaqp_spmm_tiled_pays(de - db, self.dependent_nnz)):
                 bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, db, de, p.feat.shape[0])
                 if panels:
                     self.panels_dependent = B.DevicePanels(B.adaqp_plan_spmm_panels(
                         p.rowptr, p.col, p.val, db, de, p.feat.shape[0], bounds, off, panel_min_row, panel_piece_cols), dev)
-                    ws_d = max(ws_d, B.adaqp_spmm_panels_workspace_bytes(self.panels_dependent.n_per_tile, cfg.dim))
                 self.tile_off_dependent = torch.from_numpy(off).to(dev)
                 self.tile_chunk_dependent = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)
-                ws_d = max(ws_d, B.adaqp_spmm_tiled_workspace_bytes(de - db, cfg.dim))
+                ws_d = max(ws_d, B.adaqp_spmm_tiled_workspace_bytes(de - db, cfg.dim)
+                           + B.adaqp_spmm_panels_workspace_bytes(self.panels_dependent.n_per_tile, cfg.dim))
         self.ws_overlap = torch.empty(max(ws_o, 256), dtype=torch.uint8, device=dev)
         self.ws_dependent = torch.empty(max(ws_d, 256), dtype=torch.uint8, device=dev)
         self.stream_msg = torch.cuda.Stream(device=dev)

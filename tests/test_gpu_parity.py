@@ -636,6 +636,26 @@ def test_spmm_panels(oracle, dim, ld):
     assert np.all(out[~listed] == 7.0)
     err = np.abs(out[listed, :dim].astype(np.float64) - want[listed])
     assert np.all(err <= SPMM_RTOL * mag[listed] + 1e-30)
+    # ... and the tiled kernel leaves exactly those rows alone, so the two may run at the same time: on two
+    # streams, a workspace each, the bits are those of one after the other
+    rp, cl, vl = (torch.from_numpy(x).to(DEV) for x in (rowptr, col, val))
+    Hd, offd = torch.from_numpy(H).to(DEV), torch.from_numpy(off).to(DEV)
+    ws_t = torch.empty(B.adaqp_spmm_tiled_workspace_bytes(n_rows, dim), dtype=torch.uint8, device=DEV)
+    only_tiled = torch.full((n_rows, ld), 7.0, dtype=torch.float32, device=DEV)
+    B.adaqp_spmm_csr_tiled(rp, cl, vl, 0, n_rows, Hd, dim, only_tiled, offd, ws_t)
+    torch.cuda.synchronize()
+    assert torch.all(only_tiled[torch.from_numpy(listed).to(DEV)] == 7.0)
+    one_after_the_other = only_tiled.clone()
+    B.adaqp_spmm_csr_panels(panels, 0, n_rows, Hd, dim, one_after_the_other, ws)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(device=DEV), torch.cuda.Stream(device=DEV)
+    together = torch.full((n_rows, ld), 7.0, dtype=torch.float32, device=DEV)
+    torch.cuda.synchronize()
+    B.adaqp_spmm_csr_panels(panels, 0, n_rows, Hd, dim, together, ws, stream=s2)
+    B.adaqp_spmm_csr_tiled(rp, cl, vl, 0, n_rows, Hd, dim, together, offd, ws_t, stream=s1)
+    s1.synchronize()
+    s2.synchronize()
+    assert torch.equal(together.view(torch.int32), one_after_the_other.view(torch.int32))
 
 
 def test_spmm_panels_random_shapes(oracle):
@@ -930,14 +950,21 @@ def test_layer_step_with_panels(oracle, name):
     assert np.all(np.abs(L.out.cpu().numpy().astype(np.float64) - out64) <= SPMM_RTOL * mag + 1e-30)
 
 
-@pytest.mark.parametrize("schedule_name", ["serial", "isolated"])
+@pytest.mark.parametrize("schedule_name", ["serial", "isolated", "isolated_tiled_panels", "free_tiled_panels"])
 def test_layer_step_captured_in_a_graph(schedule_name):
     """The step allocates nothing and clears nothing with memset, so it can be captured into a HIP graph; every
-    replay (with eager work and synchronisations in between) must give the bits of the eager step."""
-    schedule = {"serial": B.SERIAL, "isolated": B.ISOLATED}[schedule_name]
+    replay (with eager work and synchronisations in between) must give the bits of the eager step.  With tiles
+    and panels in both row ranges the two streams wait for each other twice more (the panel kernels run beside
+    the tiled ones)."""
+    schedule = {"serial": B.SERIAL, "isolated": B.ISOLATED, "free": B.FREE}[schedule_name.split("_")[0]]
     p = make_partition(CONFIGS["c0"])
     cfg = p.cfg
-    L = LayerStep(p, DEV, seed=99)
+    if schedule_name.endswith("tiled_panels"):
+        deg = np.diff(p.rowptr)
+        L = LayerStep(p, DEV, seed=99, tiled=True, panel_min_row=max(int(np.quantile(deg[deg > 0], 0.9)), 2))
+        assert L.panels_overlap and L.panels_dependent
+    else:
+        L = LayerStep(p, DEV, seed=99)
     L.run(schedule)
     L.synchronize()
     want_out = L.out.clone()

@@ -253,7 +253,7 @@ def test_plan_spmm_panels():
         # the rows taken are struck from the tile table, the others are untouched
         taken = np.zeros(re - rb, dtype=bool)
         taken[np.array(want_rows, dtype=np.int64) - rb] = True
-        assert np.all(off[taken] == 0) and np.array_equal(off[~taken], off0[~taken])
+        assert np.all(off[taken] == -1) and np.array_equal(off[~taken], off0[~taken])
     # nothing long enough: no plan, table untouched
     bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, 0, n_rows, n_cols)
     off0 = off.copy()
