@@ -37,13 +37,14 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c1", help="c0..c4 (c1 is the configuration the metric is quoted on)")
-    ap.add_argument("--schedule", default="isolated", choices=["serial", "isolated", "free"],
-                    help="schedule of the timed steps.  isolated (the default) is the paper's Fig. 7: the central rows "
-                         "start on the second stream once quantisation is done.  Where the aggregation is one kernel "
-                         "per row range the three take the same time on one GPU (the aggregation fills the device "
-                         "and there is no transfer to hide); where the longest rows go through the panel kernel the "
-                         "two-stream schedules run a panel kernel beside a tiled one and are faster than serial.  The "
-                         "per-kernel figures under `kernels` are always timed one launch at a time")
+    ap.add_argument("--schedule", default=None, choices=["serial", "isolated", "free"],
+                    help="schedule of the timed steps.  Default: isolated (the paper's Fig. 7: the central rows start "
+                         "on the second stream once quantisation is done) where the step pairs a panel kernel with a "
+                         "tiled kernel on its two streams, which is faster than one after the other (workload c1); "
+                         "serial elsewhere: with one aggregation kernel per row range the three schedules take the "
+                         "same time on one GPU (the aggregation fills the device and there is no transfer to hide), "
+                         "and serial keeps the per-kernel durations of a rocprofv3 trace of the run meaningful.  The "
+                         "figures under `kernels` are always timed one launch at a time")
     ap.add_argument("--kernel-reps", type=int, default=20, help="launches per kernel in the breakdown")
     ap.add_argument("--all-schedules", action="store_true",
                     help="also time 3 steps of the other two schedules (their aggregation launches overlap, which "
@@ -193,6 +194,10 @@ def main():
     t_gen = time.perf_counter() - t0
     dev = "cuda:0"
     L = LayerStep(p, dev, seed=2306, tiled=False if args.no_tiled else None, panels=not args.no_panels)
+    if args.schedule is None:
+        pairs = (not cfg.backward and L.tile_off_overlap is not None and L.tile_off_dependent is not None
+                 and bool(L.panels_overlap or L.panels_dependent))
+        args.schedule = "isolated" if pairs else "serial"
     torch.cuda.synchronize()
     sched = {"serial": B.SERIAL, "isolated": B.ISOLATED, "free": B.FREE}
 
