@@ -130,6 +130,22 @@ def test_full_size_layer_step(oracle, name):
         got = feat_after[pl.halo_idx_host]
         assert np.all(np.abs(got - sent) <= params[:, 1:2] * (1 + 1e-4) + 1e-30)
 
+    # ---- the two-stream schedules (bench.py times `isolated` where the step pairs a panel kernel with a tiled
+    # ---- one): the same bits as the serial step checked above ----
+    want_out, want_feat = L.out.clone(), L.feat.clone()
+    for schedule in (B.ISOLATED, B.FREE):
+        if not cfg.backward:
+            L.feat[cfg.n_local: cfg.n_local + cfg.n_send] = float("nan")
+        L.out.fill_(float("nan"))
+        L.recv_packed.zero_()
+        torch.cuda.synchronize()
+        L.run(schedule)
+        L.synchronize()
+        assert torch.equal(L.out.view(torch.int32), want_out.view(torch.int32)), f"schedule {schedule}: aggregate"
+        assert torch.equal(L.feat.view(torch.int32), want_feat.view(torch.int32)), f"schedule {schedule}: halo rows"
+        assert np.array_equal(L.recv_packed.cpu().numpy()[: pl.packed_bytes], packed), f"schedule {schedule}: bytes"
+    _say(f"full size {name}: isolated and free schedules give the serial step's bits")
+
 
 def test_full_size_backward_receive(oracle):
     """c4 with the receive side on: the received gradients are added to the local rows in slot order."""
