@@ -253,7 +253,8 @@ int32_t adaqp_spmm_tiled_pays(int64_t n_rows, int64_t nnz);
  * tile_off_out[(row_end - row_begin) * (ADAQP_SPMM_TILES + 1)]: entry t of a row = number of its entries that
  * belong to tiles before t.  For a row of at least ADAQP_SPMM_TILED_SHORT_ROW entries that is the number of
  * entries with column < bounds[t]; a shorter row is assigned whole to tile (row - row_begin) mod
- * ADAQP_SPMM_TILES (eight segments of one or two entries each would cost more than they save).  Errors: EINVAL (unsorted / repeated / out-of-range column, bad rowptr). */
+ * ADAQP_SPMM_TILES (eight segments of one or two entries each would cost more than they save).
+ * Errors: EINVAL (unsorted / repeated / out-of-range column, bad rowptr). */
 int adaqp_plan_spmm_tiles(const int64_t *rowptr_host, const int32_t *col_host, int64_t row_begin, int64_t row_end,
                           int64_t n_cols, int32_t *col_bounds_out, int32_t *tile_off_out);
 
@@ -269,7 +270,8 @@ int adaqp_spmm_tiled_workspace_bytes(int64_t n_rows, int32_t dim, int64_t *bytes
  * tile_off_dev: device copy of adaqp_plan_spmm_tiles' table for the same row range (planning rejects graphs
  * with out-of-range columns; should the device arrays hold one nevertheless, it is read as column 0 with
  * coefficient 0).  A row whose table entries are negative (struck by adaqp_plan_spmm_panels) is skipped: its
- * row of out is not written.  A table that disagrees with rowptr is clamped to the row (wrong sums, no stray access).  The summation order is fixed by the table and the launch geometry: runs are bit-identical.
+ * row of out is not written.  A table that disagrees with rowptr is clamped to the row (wrong sums, no stray
+ * access).  The summation order is fixed by the table and the launch geometry: runs are bit-identical.
  * H and out must be line-padded (pitch a multiple of 32 floats, base 128-byte aligned); the padding of the
  * written rows is set to zero.  chunk_cols: 64, 128 or 0 (= 128), see adaqp_spmm_tiled_chunk_cols; the result's
  * bits depend on it.  workspace_dev: 256-byte aligned, >= adaqp_spmm_tiled_workspace_bytes.

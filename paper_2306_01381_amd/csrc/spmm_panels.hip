@@ -249,10 +249,11 @@ extern "C" int adaqp_plan_spmm_panels(const int64_t *rowptr_host, const int32_t 
             if (len > 0) {
                 const int64_t ng = (len + 7) / 8;
                 if (n_groups + ng > INT32_MAX - 1) return ADAQP_ESIZE;
-                if (fill && n_groups + ng > sizes_out[2]) return ADAQP_EINVAL;  // the arrays were sized for another plan
+                if (fill && n_groups + ng > sizes_out[2]) return ADAQP_EINVAL;      // arrays sized for another plan
                 if (fill) {
                     for (int64_t k = 0; k < ng * 8; ++k) {
-                        const int32_t c = distinct[at + (size_t)std::min<int64_t>(k, len - 1)];   // padding repeats the last column
+                        // padding repeats the last column (with coefficient 0)
+                        const int32_t c = distinct[at + (size_t)std::min<int64_t>(k, len - 1)];
                         const int64_t G = n_groups * 8 + k;
                         const int64_t g = G / 8, h = G % 2, u = (G % 8) / 2;
                         pcol_out[(g * 2 + h) * 4 + u] = c;
