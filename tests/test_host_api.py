@@ -269,6 +269,42 @@ def test_plan_spmm_panels():
                                  0, 1, 8, np.zeros(9, np.int32), None, 1, 8)                    # repeated column
 
 
+def test_plan_spmm_panels_random_graphs():
+    """Seeded sweep: whatever the shape, the plan decodes back to exactly the rows it took."""
+    rng = np.random.default_rng(2024)
+    for case in range(12):
+        n_rows = int(rng.choice([1, 5, 33, 64, 130]))
+        n_cols = int(rng.choice([1, 7, 8, 9, 40, 257]))
+        degs = rng.integers(0, n_cols + 1, size=n_rows)
+        if case % 3 == 0:
+            degs[:] = n_cols                                            # dense
+        rowptr = np.zeros(n_rows + 1, dtype=np.int64)
+        cols = []
+        for r in range(n_rows):
+            cols.append(np.sort(rng.choice(n_cols, size=int(degs[r]), replace=False)))
+            rowptr[r + 1] = rowptr[r] + degs[r]
+        col = np.concatenate(cols).astype(np.int32)
+        val = (rng.standard_normal(len(col)) + 3.0).astype(np.float32)  # never zero
+        rb = int(rng.integers(0, n_rows))
+        re = int(rng.integers(rb, n_rows + 1))
+        min_len = int(rng.choice([1, 2, 5, 30]))
+        piece_cols = int(rng.choice([8, 16, 64]))
+        bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, rb, re, n_cols)
+        plan = B.adaqp_plan_spmm_panels(rowptr, col, val, rb, re, n_cols, bounds, off, min_len, piece_cols)
+        want_rows = [r for r in range(rb, re) if degs[r] >= min_len]
+        if not want_rows:
+            assert plan is None, case
+            continue
+        assert sorted(plan["panel_rows"][plan["panel_rows"] >= 0].tolist()) == want_rows, case
+        dense, seen = _decode_panels(plan, n_cols)
+        assert len(seen) == plan["n_panel_pieces"], case
+        for k, r in enumerate(plan["panel_rows"]):
+            want = np.zeros(n_cols)
+            if r >= 0:
+                want[col[rowptr[r]: rowptr[r + 1]]] = val[rowptr[r]: rowptr[r + 1]]
+            assert np.array_equal(dense[k], want), (case, k, r)
+
+
 def test_layer_desc_mirror_matches_the_library():
     import ctypes
     assert int(B.lib().adaqp_layer_desc_bytes()) == ctypes.sizeof(B.LayerDesc)
