@@ -83,6 +83,21 @@ def test_argument_errors_are_caught_before_any_launch():
     d = B.LayerDesc()
     d.direction = 7
     assert L.adaqp_layer_step(ctypes.byref(d)) == B.EINVAL
+    # panels: nothing to do is fine, anything inconsistent is refused on the host
+    assert L.adaqp_spmm_csr_panels(None, 0, 4, one, 8, 32, 8, one, 32, one, 1 << 20, None) == B.EINVAL
+    none = B.SpmmPanels()
+    assert L.adaqp_spmm_csr_panels(ctypes.byref(none), 0, 4, one, 8, 32, 8, one, 32, one, 1 << 20, None) == B.OK
+    some = B.SpmmPanels(1, 1, 1, 1, 256, 256, 256, 256, 256, 256)
+    assert L.adaqp_spmm_csr_panels(ctypes.byref(some), 0, 4, one, 8, 32, 8, one, 32, one, 16, None) == B.ESIZE
+    assert L.adaqp_spmm_csr_panels(ctypes.byref(some), 0, 4, one, 8, 24, 8, one, 32, one, 1 << 20, None) == B.EINVAL  # pitch
+    assert L.adaqp_spmm_csr_panels(ctypes.byref(some), 0, 4, one, 8, 32, 8, one, 32, None, 1 << 20, None) == B.EINVAL
+    assert L.adaqp_spmm_csr_panels(ctypes.byref(some), 4, 0, one, 8, 32, 8, one, 32, one, 1 << 20, None) == B.EINVAL
+    holes = B.SpmmPanels(1, 1, 1, 1, 256, 0, 256, 256, 256, 256)                    # an array missing
+    assert L.adaqp_spmm_csr_panels(ctypes.byref(holes), 0, 4, one, 8, 32, 8, one, 32, one, 1 << 20, None) == B.EINVAL
+    many = B.SpmmPanels(1, 1, 1, 9, 256, 256, 256, 256, 256, 256)                   # more pieces than piece slots
+    assert L.adaqp_spmm_csr_panels(ctypes.byref(many), 0, 4, one, 8, 32, 8, one, 32, one, 1 << 20, None) == B.EINVAL
+    bad = B.SpmmPanels(-1, 0, 0, 0, 0, 0, 0, 0, 0, 0)
+    assert L.adaqp_spmm_csr_panels(ctypes.byref(bad), 0, 4, one, 8, 32, 8, one, 32, one, 1 << 20, None) == B.EINVAL
 
 
 def test_workspace_query():
