@@ -12,7 +12,7 @@ import numpy as np
 import torch
 
 from . import binding as B
-from .synth import Partition
+from .synth import Partition, alpha_sq_stand_in
 
 _hip: Optional[ctypes.CDLL] = None
 
@@ -116,12 +116,10 @@ class LayerStep:
         self.packed = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
         self.params = torch.zeros((max(n, 1), 2), dtype=torch.float32, device=dev)
         # trace for the bit-width assigner: per slot, the sum of squared coefficients the message meets on its
-        # target device is an input; the stand-in used here is the sum of squared coefficients of the node's own row
+        # target device is an input (the generator supplies a stand-in)
         self.alpha_sq = self.beta = None
         if trace and n > 0:
-            sq = np.add.reduceat(np.square(p.val.astype(np.float64)), np.minimum(p.rowptr[:-1], max(p.nnz - 1, 0)))
-            sq[np.diff(p.rowptr) == 0] = 0.0
-            self.alpha_sq_host = sq[self.plan.send_idx_host].astype(np.float32)
+            self.alpha_sq_host = np.ascontiguousarray(alpha_sq_stand_in(p)[self.plan.perm])
             self.alpha_sq = torch.from_numpy(self.alpha_sq_host).to(dev)
             self.beta = torch.zeros(n, dtype=torch.float32, device=dev)
         self.recv_packed = torch.zeros(nbytes, dtype=torch.uint8, device=dev)

@@ -17,7 +17,7 @@ from typing import Dict, Optional
 
 import numpy as np
 
-__all__ = ["PartitionConfig", "Partition", "CONFIGS", "make_partition", "config_by_name"]
+__all__ = ["PartitionConfig", "Partition", "CONFIGS", "make_partition", "config_by_name", "alpha_sq_stand_in"]
 
 
 @dataclass(frozen=True)
@@ -254,3 +254,12 @@ def make_partition(cfg: PartitionConfig, seed: Optional[int] = None) -> Partitio
                      n_central=n_central, feat=dy,
                      send_idx=send_rows.astype(np.int32), peer_of_slot=peer_of_slot, bits=bits,
                      halo_idx=dst, meta={"direction": "backward"})
+
+
+def alpha_sq_stand_in(p: Partition) -> np.ndarray:
+    """Input stand-in for the trace of Sec. 4.2: per send slot, the sum of squared aggregation coefficients the
+    message meets on its target device.  That sum lives on the peer, which this one-partition workload does not
+    have; the sum over the sending node's own CSR row takes its place (float32 [n_send], input slot order)."""
+    sq = np.add.reduceat(np.square(p.val.astype(np.float64)), np.minimum(p.rowptr[:-1], max(p.nnz - 1, 0)))
+    sq[np.diff(p.rowptr) == 0] = 0.0
+    return sq[p.send_idx].astype(np.float32)

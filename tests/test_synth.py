@@ -1,7 +1,11 @@
 """The seeded input generators: structure and determinism."""
 import hashlib
+import importlib.util
+import json
+import os
 
 import numpy as np
+import pytest
 
 from paper_2306_01381_amd.synth import CONFIGS, make_partition
 
@@ -11,6 +15,24 @@ def _digest(p):
     for a in (p.rowptr, p.col, p.val, p.feat, p.send_idx, p.peer_of_slot, p.bits, p.halo_idx):
         h.update(np.ascontiguousarray(a).tobytes())
     return h.hexdigest()
+
+
+def _golden():
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_synth_digest", os.path.join(here, "make_synth_digest.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    with open(os.path.join(here, "synth_digest.json")) as f:
+        return mod.digest, json.load(f)
+
+
+@pytest.mark.parametrize("name", ["c0", "c3"])
+def test_generated_workload_matches_its_stored_digest(name):
+    """The partitions the benchmark and the full-size parity tests run on are pinned by stored digests (sizes,
+    column checksums, one SHA-256 per array).  c1, c2 and c4 take a minute to draw: their digests are checked
+    where they are generated anyway, in the full-size GPU tests."""
+    digest, stored = _golden()
+    assert digest(make_partition(CONFIGS[name])) == stored[name]
 
 
 def test_c0_structure():
