@@ -27,8 +27,9 @@
  *     produced, but the kernels never touch memory outside the stated extents: a slot whose row index,
  *     width or offset is out of range is skipped, an edge whose column is out of range is skipped.
  *   - A count of zero is a successful no-op.
- *   - Inputs must be finite.  A row's range max - min must be 0 or at least 2^-100 (otherwise the fp32
- *     reciprocal overflows; codes stay in range but are unspecified).
+ *   - Inputs must be finite; denormal values and ranges are handled like any other.  A row whose range
+ *     max - min is so small that (2^b - 1) / range is not an fp32 number (below about 2^-120) is quantised as a
+ *     constant row: S = 0, every code 0, de-quantised to Z.
  *   - Feature matrices are fp32 row-major with a leading dimension (pitch) ld >= dim, counted in elements.
  *   - Preferred layout ("line-padded"): base pointer 128-byte aligned and ld a multiple of 32, so that every
  *     row starts on a 128-byte line and covers whole lines.  Any other layout is accepted and gives the same
@@ -88,7 +89,8 @@ int adaqp_plan_layout(int64_t n, int32_t dim, const uint8_t *bits_host, const in
 /* ---------------------------------------------------------------------------------------------------- */
 
 /* For each slot s in [0, n_send):  h = feat[send_idx[s], 0:dim],  b = bits[s],  L = 2^b - 1
- *     Z = min(h) + 0.0f,  range = (max(h) + 0.0f) - Z,  S = range / L,  inv = L / range   (S = inv = 0 if range == 0)
+ *     Z = min(h) + 0.0f,  range = (max(h) + 0.0f) - Z,  S = range / L,  inv = L / range   (S = inv = 0 if range == 0
+ *     or inv overflows)
  *     x_j = min((h_j - Z) * inv, L);  t_j = trunc(x_j * 2^16);  code_j = (t_j + r16(seed, s, j)) >> 16
  *     params[s] = {Z, S};  code_j is stored in bits [j*b, j*b+b) of the row at packed + row_offset[s]
  *     (little-endian bit string, zero padded to adaqp_row_stride(dim, b) bytes).

@@ -24,7 +24,9 @@
  *   R3  r comes from Philox4x32-10 keyed by the seed, counter = (column / 8, slot low, slot high, tag); the
  *       128 output bits serve eight consecutive columns as eight 16-bit slices.
  *   R4  a constant row has S = 0, inv = 0, all codes 0; min and max are passed through "+ 0.0f" so that a
- *       row holding both -0 and +0 has one well-defined zero-point.
+ *       row holding both -0 and +0 has one well-defined zero-point.  A row whose range is so small that
+ *       (2^b-1)/(max-min) overflows fp32 (range below about 2^-120) is treated as constant as well: Eq. 4 has
+ *       no finite argument for it in fp32, and its de-quantisation error stays below that range.
  *   R5  codes are laid down little-endian: column j occupies bits [j*b, j*b + b) of the row's bit string,
  *       bit k of the string is bit (k mod 8) of byte (k / 8).  A row occupies 4 * ceil(dim*b/32) bytes, unused
  *       bits are zero.
@@ -37,6 +39,7 @@
  * round trips, Philox known-answer vectors, dense brute-force A*H and special matrices for the SpMM.
  * Nothing in this file is "parity unpinned".
  */
+#include <float.h>
 #include <math.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -149,6 +152,10 @@ int oracle_quantize_pack(const float *feat, int64_t ld, int32_t dim,
         if (range > 0.0f) {
             S = range / levels;                    /* Eq. 4: scale */
             inv = levels / range;                  /* R1 */
+            if (!(inv <= FLT_MAX)) {               /* R4: range below (2^b-1)/FLT_MAX, the reciprocal is not an fp32 */
+                S = 0.0f;                          /* number - the row counts as constant */
+                inv = 0.0f;
+            }
         }
         params[2 * s + 0] = Z;                     /* R6 */
         params[2 * s + 1] = S;

@@ -91,11 +91,14 @@ __device__ __forceinline__ void store_vec(float *p, const float *src)
 }
 
 // Codes of one granule (8 columns) at width B, merged little-endian into lo (and hi for B == 8).
-// inv16 = inv * 2^16 and levels16 = (2^B - 1) * 2^16: scaling by a power of two commutes with fp32 rounding,
-// so trunc(min((x - Z) * inv, L) * 2^16) == trunc(min((x - Z) * inv16, levels16)) whenever inv16 is finite.
+// The definition is trunc(min((x - Z) * inv, L) * 2^16).  With scale = inv * 2^16 and top = L * 2^16 the last
+// multiplication folds into the first: scaling by a power of two commutes with fp32 rounding, so
+// trunc(min((x - Z) * scale, top)) is the same integer - as long as inv * 2^16 is an fp32 number.  For the rare
+// row where it overflows (range below about 2^-104) TWO_STEP takes the definition as written, with scale = inv
+// and top = L; for every other row the two forms agree, so a wave may take either for all its rows.
 // MASK: zero the codes of columns >= dim (only the last granule step of a row can need it).
-template <int B, bool MASK>
-__device__ __forceinline__ void quantise_granule(const float (&x)[8], float Z, float inv16, float levels16,
+template <int B, bool MASK, bool TWO_STEP>
+__device__ __forceinline__ void quantise_granule(const float (&x)[8], float Z, float scale, float top,
                                                  const Rand128 &rnd, int32_t col0, int32_t dim,
                                                  uint32_t &lo, uint32_t &hi)
 {
@@ -104,8 +107,9 @@ __device__ __forceinline__ void quantise_granule(const float (&x)[8], float Z, f
     hi = 0u;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-        float pos = (x[k] - Z) * inv16;                       // Eq. 4 argument in 16.16 fixed point, >= 0
-        pos = fminf(pos, levels16);                           // the top element may overshoot by an ulp
+        float pos = (x[k] - Z) * scale;                       // Eq. 4 argument (in 16.16 fixed point), >= 0
+        pos = fminf(pos, top);                                // the top element may overshoot by an ulp
+        if (TWO_STEP) pos = pos * 65536.0f;
         const uint32_t fixed = (uint32_t)pos;                 // truncated
         const uint32_t r16 = (k & 1) ? (words[k >> 1] >> 16) : (words[k >> 1] & 0xFFFFu);
         uint32_t code = (fixed + r16) >> 16;                  // App. A.1: up with probability frac
@@ -133,7 +137,9 @@ __device__ __forceinline__ void store_granule(uint8_t *row, int32_t g, int32_t n
     }
 }
 
-struct RowScale { float Z, S, inv16, range; };
+struct RowScale { float Z, S, inv, inv16, range; };
+
+constexpr float kFltMax = 3.402823466e+38f;
 
 __device__ __forceinline__ RowScale row_scale(float mn, float mx, float levels)
 {
@@ -142,10 +148,15 @@ __device__ __forceinline__ RowScale row_scale(float mn, float mx, float levels)
     const float range = (mx + 0.0f) - rs.Z;
     rs.range = range;
     rs.S = 0.0f;
+    rs.inv = 0.0f;
     rs.inv16 = 0.0f;
     if (range > 0.0f) {
-        rs.S = range / levels;            // Eq. 4 scale, correctly rounded fp32 division
-        rs.inv16 = (levels / range) * 65536.0f;
+        const float inv = levels / range;
+        if (inv <= kFltMax) {             // else: the reciprocal is not an fp32 number, the row counts as constant
+            rs.S = range / levels;        // Eq. 4 scale, correctly rounded fp32 division
+            rs.inv = inv;
+            rs.inv16 = inv * 65536.0f;    // may overflow: then the wave takes the two-step form
+        }
     }
     return rs;
 }
@@ -158,20 +169,34 @@ __device__ __forceinline__ float trace_beta(float alpha_sq, int32_t dim, float r
     return (wd * r2) / 6.0f;
 }
 
-template <int B, int GPL>
+template <int B, int GPL, bool TWO_STEP>
 __device__ __forceinline__ void quantise_row(const float (&x)[GPL][8], const Rand128 (&rnd)[GPL],
                                              const RowScale &rs, int lpr, int l, int32_t dim, int32_t n_granules,
                                              uint8_t *row, int64_t stride, bool valid)
 {
-    const float levels16 = (float)((1 << B) - 1) * 65536.0f;
+    const float levels = (float)((1 << B) - 1);
+    const float scale = TWO_STEP ? rs.inv : rs.inv16;
+    const float top = TWO_STEP ? levels : levels * 65536.0f;
 #pragma unroll
     for (int i = 0; i < GPL; ++i) {
         const int32_t g = i * lpr + l;
         uint32_t lo, hi;
-        if (i < GPL - 1) quantise_granule<B, false>(x[i], rs.Z, rs.inv16, levels16, rnd[i], g * 8, dim, lo, hi);
-        else             quantise_granule<B, true>(x[i], rs.Z, rs.inv16, levels16, rnd[i], g * 8, dim, lo, hi);
+        if (i < GPL - 1) quantise_granule<B, false, TWO_STEP>(x[i], rs.Z, scale, top, rnd[i], g * 8, dim, lo, hi);
+        else             quantise_granule<B, true, TWO_STEP>(x[i], rs.Z, scale, top, rnd[i], g * 8, dim, lo, hi);
         if (valid && g < n_granules) store_granule<B>(row, g, n_granules, stride, lo, hi);
     }
+}
+
+// The widths of a wave's rows: slots are sorted by (peer, width), so nearly every wave holds a single width and
+// takes one of the three bodies; a wave on a seam runs the bodies of the widths it holds, each under its lanes.
+template <int GPL, bool TWO_STEP>
+__device__ __forceinline__ void quantise_rows(const float (&x)[GPL][8], const Rand128 (&rnd)[GPL],
+                                              const RowScale &rs, int lpr, int l, int32_t dim, int32_t n_granules,
+                                              uint8_t *row, int64_t stride, bool valid, int32_t b)
+{
+    if (b == 4)      quantise_row<4, GPL, TWO_STEP>(x, rnd, rs, lpr, l, dim, n_granules, row, stride, valid);
+    else if (b == 2) quantise_row<2, GPL, TWO_STEP>(x, rnd, rs, lpr, l, dim, n_granules, row, stride, valid);
+    else if (b == 8) quantise_row<8, GPL, TWO_STEP>(x, rnd, rs, lpr, l, dim, n_granules, row, stride, valid);
 }
 
 // Pins a value to this point of the program: the optimiser may neither sink its computation below nor
@@ -270,29 +295,20 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
         mn = fminf(mn, __shfl_xor(mn, m, kWave));
         mx = fmaxf(mx, __shfl_xor(mx, m, kWave));
     }
-    const uint64_t valid_mask = __ballot(valid);
-    if (valid_mask == 0) return;
-    const int32_t b_first = __builtin_amdgcn_readlane(b, __ffsll((long long)valid_mask) - 1);
-    const bool one_width = __ballot(valid && b != b_first) == 0;       // no cross-lane operation below this line
+    if (__ballot(valid) == 0) return;
 
     const float levels = (float)((1 << (b & 15)) - 1);
     const RowScale rs = row_scale(mn, mx, levels);
+    // a row whose scale overflows once the 2^16 is folded in sends its whole wave down the two-step form
+    const bool two_step = __ballot(valid && !(rs.inv16 <= kFltMax)) != 0;      // no cross-lane operation below
     if (valid && l == 0) {
         *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
         if (a.beta) a.beta[s] = trace_beta(a.alpha_sq[s], a.dim, rs.range);
     }
 
-    // codes.  Slots are sorted by (peer, width), so nearly every wave holds a single width.
     uint8_t *row = a.packed + (valid ? off : 0);
-    if (one_width) {
-        if (b_first == 4)      quantise_row<4, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
-        else if (b_first == 2) quantise_row<2, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
-        else                   quantise_row<8, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
-    } else {
-        if (b == 4)      quantise_row<4, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
-        else if (b == 2) quantise_row<2, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
-        else if (b == 8) quantise_row<8, GPL>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid);
-    }
+    if (!two_step) quantise_rows<GPL, false>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid, b);
+    else           quantise_rows<GPL, true>(x, rnd, rs, lpr, l, a.dim, a.n_granules, row, stride, valid, b);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -324,8 +340,10 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_wide_kernel(const QuantA
         mx = fmaxf(mx, __shfl_xor(mx, m, kWave));
     }
     const float levels = (float)((1 << b) - 1);
-    const float levels16 = levels * 65536.0f;
     const RowScale rs = row_scale(mn, mx, levels);
+    const bool two_step = !(rs.inv16 <= kFltMax);                       // wave-uniform: one row per wave
+    const float scale = two_step ? rs.inv : rs.inv16;
+    const float top = two_step ? levels : levels * 65536.0f;
     if (lane == 0) {
         *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(rs.Z, rs.S);
         if (a.beta) a.beta[s] = trace_beta(a.alpha_sq[s], a.dim, rs.range);
@@ -340,13 +358,16 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_wide_kernel(const QuantA
         const Rand128 rnd = philox4x32_10((uint32_t)g, s_lo, s_hi, kCounterTag, a.seed_lo, a.seed_hi);
         uint32_t lo, hi;
         if (b == 4) {
-            quantise_granule<4, true>(x, rs.Z, rs.inv16, levels16, rnd, g * 8, a.dim, lo, hi);
+            if (two_step) quantise_granule<4, true, true>(x, rs.Z, scale, top, rnd, g * 8, a.dim, lo, hi);
+            else          quantise_granule<4, true, false>(x, rs.Z, scale, top, rnd, g * 8, a.dim, lo, hi);
             store_granule<4>(row, g, a.n_granules, stride, lo, hi);
         } else if (b == 2) {
-            quantise_granule<2, true>(x, rs.Z, rs.inv16, levels16, rnd, g * 8, a.dim, lo, hi);
+            if (two_step) quantise_granule<2, true, true>(x, rs.Z, scale, top, rnd, g * 8, a.dim, lo, hi);
+            else          quantise_granule<2, true, false>(x, rs.Z, scale, top, rnd, g * 8, a.dim, lo, hi);
             store_granule<2>(row, g, a.n_granules, stride, lo, hi);
         } else {
-            quantise_granule<8, true>(x, rs.Z, rs.inv16, levels16, rnd, g * 8, a.dim, lo, hi);
+            if (two_step) quantise_granule<8, true, true>(x, rs.Z, scale, top, rnd, g * 8, a.dim, lo, hi);
+            else          quantise_granule<8, true, false>(x, rs.Z, scale, top, rnd, g * 8, a.dim, lo, hi);
             store_granule<8>(row, g, a.n_granules, stride, lo, hi);
         }
     }

@@ -113,6 +113,52 @@ def test_codec_single_width_and_seeds(oracle, b):
                     np.zeros(64, np.int32), 1, seed)
 
 
+@pytest.mark.parametrize("dim,ld", [(24, 24), (602, 608), (300, 320), (5000, 5000)])
+def test_codec_tiny_ranges_and_signed_zeros(oracle, dim, ld):
+    """Rows at the bottom of fp32 (ranges from 1e-30 down to the smallest denormal: the scale with the 2^16 folded
+    in overflows, then the reciprocal itself), rows whose minimum is reached by both -0.0 and +0.0, constant rows
+    of either zero - next to ordinary rows in the same waves, every width."""
+    _say(f"codec tiny ranges dim={dim} ld={ld}")
+    rng = np.random.default_rng(dim)
+    scales = [1.0, 1e-30, 1e-33, 1e-36, 3e-38, 1e-39, 1e-42, 3e-45, 1e-3]
+    n_rows = 6 * len(scales)
+    feat = np.zeros((n_rows, ld), dtype=np.float32)
+    for i, sc in enumerate(scales):
+        u = rng.random((6, dim))
+        u[:, 0], u[:, -1] = 0.0, 1.0
+        base = np.array([0.0, sc * 8, -sc * 3, 1e-20, 0.0, 0.0])[:, None]
+        rows = (base + u * sc).astype(np.float32)
+        rows[4] = np.float32(sc)
+        rows[5, 1:] = rows[5, 0]
+        if dim > 1:
+            rows[5, 1] = np.nextafter(rows[5, 0], np.float32(1), dtype=np.float32)
+        feat[6 * i: 6 * i + 6, :dim] = rows
+    zeros = np.zeros((6, ld), dtype=np.float32)
+    zeros[0, :dim] = np.maximum(rng.standard_normal(dim), 0)      # ReLU-like row: minimum +0.0 ...
+    zeros[0, dim // 2] = -0.0                                      # ... and -0.0
+    zeros[0, 0] = 0.0
+    zeros[1, :dim] = -np.maximum(rng.standard_normal(dim), 0)     # maximum reached by both zeros
+    zeros[1, 0] = 0.0
+    zeros[1, dim - 1] = -0.0
+    zeros[2, :dim] = -0.0                                          # constant -0.0
+    zeros[3, :dim] = 0.0
+    zeros[3, dim - 1] = -0.0                                       # "constant" row holding both zeros
+    zeros[4, :dim] = rng.standard_normal(dim).astype(np.float32)
+    zeros[5, :dim] = np.where(rng.random(dim) < 0.5, 0.0, -0.0)   # a mixture of the two zeros only
+    feat = np.concatenate([feat, zeros], 0)
+    n_rows = feat.shape[0]                                         # the rows that are sent
+    feat = np.concatenate([feat, rng.standard_normal((2 * n_rows, ld), dtype=np.float32)], 0)   # room to receive
+    feat[:, dim:] = np.float32(1e30)
+    for b in (2, 4, 8):
+        send = np.concatenate([np.arange(n_rows), rng.permutation(n_rows)]).astype(np.int32)
+        bits = np.full(send.shape[0], b, np.uint8)
+        _codec_case(oracle, feat, dim, send, bits, np.zeros(send.shape[0], np.int32), 1, seed=17 + b)
+    send = np.tile(np.arange(n_rows), 3).astype(np.int32)
+    bits = rng.choice(np.array([2, 4, 8], dtype=np.uint8), size=send.shape[0])
+    peer = np.sort(rng.integers(0, 2, size=send.shape[0])).astype(np.int32)
+    _codec_case(oracle, feat, dim, send, bits, peer, 2, seed=99)
+
+
 def test_codec_c0(oracle):
     _say("codec c0")
     p = make_partition(CONFIGS["c0"])

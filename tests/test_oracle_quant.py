@@ -81,6 +81,53 @@ def test_code_range_and_endpoints(oracle):
             assert not np.signbit(params[6, 0])
 
 
+def _tiny_range_rows(scale, dim=24, seed=0):
+    """Rows whose range is about `scale` around offsets of very different size (0, tiny, ordinary)."""
+    rng = np.random.default_rng(seed)
+    u = rng.random((6, dim))
+    u[:, 0], u[:, 1] = 0.0, 1.0                                # the row's minimum and maximum
+    base = np.array([0.0, scale * 8, -scale * 3, 1e-20, 0.0, 0.0])[:, None]
+    rows = (base + u * scale).astype(np.float32)
+    rows[4] = np.float32(scale)                                # constant row at that size
+    rows[5, 1:] = rows[5, 0]                                   # all equal ...
+    rows[5, 1] = np.nextafter(rows[5, 0], np.float32(1), dtype=np.float32)     # ... but one element one ulp up
+    return rows
+
+
+@pytest.mark.parametrize("scale", [1e-30, 1e-33, 1e-36, 3e-38, 1e-39, 1e-42, 3e-45])
+def test_tiny_and_denormal_ranges(oracle, scale):
+    """Eq. 4 at the bottom of fp32: ranges down to denormals.  Either the reciprocal (2^b-1)/range is an fp32
+    number and the row is quantised as any other (minimum -> 0, maximum -> 2^b-1, every code within one step of
+    the float64 quotient), or it overflows and the row counts as constant (S = 0, codes 0, de-quantised = Z)."""
+    flt_max = float(np.finfo(np.float32).max)
+    for b in WIDTHS:
+        L = (1 << b) - 1
+        rows = _tiny_range_rows(scale)
+        for seed in (0, 1, 12345):
+            packed, params, codes, off = _single_width(oracle, rows, b, seed)
+            assert codes.max() <= L
+            Z = params[:, 0].astype(np.float64)
+            S = params[:, 1].astype(np.float64)
+            mn, mx = rows.min(1), rows.max(1)
+            rng32 = (mx + np.float32(0)) - (mn + np.float32(0))          # exact in fp32 here (Sterbenz or denormal)
+            assert np.array_equal(params[:, 0], mn + np.float32(0))
+            for r in range(rows.shape[0]):
+                rr = float(rng32[r])
+                if rr == 0.0 or L / rr > flt_max:                        # constant, or treated as constant
+                    assert S[r] == 0.0 and np.all(codes[r] == 0), (scale, b, r)
+                    continue
+                assert S[r] == float(np.float32(rng32[r]) / np.float32(L))
+                assert codes[r, rows[r].argmin()] == 0 and codes[r, rows[r].argmax()] == L, (scale, b, r)
+                x = (rows[r].astype(np.float64) - Z[r]) * (L / rr)       # exact quotient position, float64
+                assert np.all(np.abs(codes[r] - x) < 1.0 + 1e-3), (scale, b, r)
+            out = np.full_like(rows, np.nan)
+            n = rows.shape[0]
+            oracle.unpack_dequant(packed, params, np.full(n, b, np.uint8), off, np.arange(n, dtype=np.int32),
+                                  rows.shape[1], out)
+            assert np.all(np.abs(out.astype(np.float64) - rows) <= np.maximum(S, rng32.astype(np.float64))[:, None]
+                          * (1 + 1e-3) + 1e-45)
+
+
 def test_overshoot_of_top_element_is_clamped(oracle):
     # search for rows where (max - Z) * inv rounds above 2^b - 1 in fp32: the clamp must still give code L
     rng = np.random.default_rng(3)
