@@ -198,9 +198,9 @@ def test_unbiased_and_variance_bounded_over_1e5_seeds(oracle, b):
     (reading R2) adds a bias of at most 2^-16 * S."""
     N = 100_000
     rng = np.random.default_rng(100 + b)
-    rows = rng.standard_normal((3, 64), dtype=np.float32)
-    rows[1] = np.maximum(rows[1], 0)
-    rows[2] *= np.float32(1e-3)
+    rows = rng.standard_normal((12, 64), dtype=np.float32)
+    rows[1::3] = np.maximum(rows[1::3], 0)
+    rows[2::3] *= np.float32(1e-3)
     mean, var, params = _moments_over_seeds(oracle, rows, b, N)
     Z = params[:, :1].astype(np.float64)
     S = params[:, 1:].astype(np.float64)
@@ -209,8 +209,10 @@ def test_unbiased_and_variance_bounded_over_1e5_seeds(oracle, b):
     sigma = S * np.sqrt(f * (1 - f) / N)
     slack = S * 2.0 ** -16 + 4 * np.spacing(np.abs(rows).astype(np.float32)).astype(np.float64)
     err = np.abs(mean - rows)
+    # 768 elements: 0.27 % of them (two) lie outside 3 sigma by chance; 1 % leaves room for seven, which a correct
+    # implementation exceeds about once in a thousand draws of the rows; none may lie outside 5 sigma
     assert np.all(err <= 5 * sigma + slack)
-    assert np.mean(err > 3 * sigma + slack) <= 0.02
+    assert np.mean(err > 3 * sigma + slack) <= 0.01
     assert np.all(var <= S * S / 4 * 1.02 + 1e-30)
     # the Bernoulli variance itself: S^2 f (1 - f), to a few per cent where it is not tiny
     expect = S * S * f * (1 - f)
