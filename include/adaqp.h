@@ -198,6 +198,25 @@ int adaqp_spmm_csr(const int64_t *rowptr_dev, const int32_t *col_dev, const floa
                    float *out_dev, int64_t ldo,
                    void *workspace_dev, int64_t workspace_bytes, void *stream);
 
+/* adaqp_spmm_csr for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same
+ * launch geometry and therefore the same bits as adaqp_spmm_csr, but the carry scratch is a buffer of
+ * ADAQP_SPMM_NOALLOC_SCRATCH_BYTES that is built into the library (one copy per GPU, held until the process
+ * ends).  The call allocates and frees nothing.  The first call on a GPU looks the buffer's address up once (make
+ * that call outside a capture).
+ *   Limit: adaqp_spmm_workspace_bytes(row_end - row_begin, nnz_range or nnz, dim) must not exceed
+ *          ADAQP_SPMM_NOALLOC_SCRATCH_BYTES, else ESIZE and nothing is launched.
+ *   Every call on a GPU uses that GPU's one buffer: two calls that may run at the same time on one GPU (two
+ *   streams, two threads) race on it - order them, or give one of them adaqp_spmm_csr with its own workspace.
+ *   The buffer keeps the last call's contents; nothing in it needs to start at zero (every piece writes its
+ *   carry slot's row number before the fix-up kernel reads it).
+ * Errors: as adaqp_spmm_csr. */
+#define ADAQP_SPMM_NOALLOC_SCRATCH_BYTES (64 << 20)
+int adaqp_spmm_csr_noalloc(const int64_t *rowptr_dev, const int32_t *col_dev, const float *val_dev, int64_t nnz,
+                           int64_t row_begin, int64_t row_end, int64_t nnz_range,
+                           const float *H_dev, int64_t n_cols, int64_t ldh, int32_t dim,
+                           float *out_dev, int64_t ldo, void *stream);
+
 /* Host only: bit-widths for the next period from the traced beta values (Sec. 4.2).  Per device pair the
  * messages are sorted by descending beta (ties: ascending slot) and cut into groups of group_size that share a
  * width (the last group of a pair may be shorter).  The widths minimise, over the assignments a greedy search

@@ -88,6 +88,8 @@ _SIGNATURES = {
     "adaqp_spmm_workspace_bytes": (ctypes.c_int, [_i64, _i64, _i32, ctypes.POINTER(_i64)]),
     "adaqp_spmm_csr": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
                                       _vp, _i64, _vp, _i64, _vp]),
+    "adaqp_spmm_csr_noalloc": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
+                                              _vp, _i64, _vp]),
     "adaqp_plan_spmm_tiles": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i64, _vp, _vp]),
     "adaqp_spmm_tiled_workspace_bytes": (ctypes.c_int, [_i64, _i32, _vp]),
     "adaqp_spmm_tiled_pays": (_i32, [_i64, _i64]),
@@ -273,6 +275,20 @@ def adaqp_spmm_csr(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, r
                                 hp, n_cols, ldh, dim, op, ldo, _dev(workspace, torch.uint8, "workspace"),
                                 workspace.numel(), _stream(stream)),
            "adaqp_spmm_csr")
+
+
+SPMM_NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def adaqp_spmm_csr_noalloc(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, row_begin: int, row_end: int,
+                           H: torch.Tensor, dim: int, out: torch.Tensor, nnz_range: int = -1,
+                           stream: Optional[torch.cuda.Stream] = None) -> None:
+    hp, n_cols, ldh = _matrix(H, "H")
+    op, _, ldo = _matrix(out, "out")
+    _check(lib().adaqp_spmm_csr_noalloc(_dev(rowptr, torch.int64, "rowptr"), _dev(col, torch.int32, "col"),
+                                        _dev(val, torch.float32, "val"), col.numel(), row_begin, row_end, nnz_range,
+                                        hp, n_cols, ldh, dim, op, ldo, _stream(stream)),
+           "adaqp_spmm_csr_noalloc")
 
 
 SPMM_TILES = 8

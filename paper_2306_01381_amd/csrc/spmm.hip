@@ -16,6 +16,8 @@
 //
 // The kernel is a gather: per entry it reads 8 bytes of (col, alpha) and 4*dim bytes of H.  It is bound by
 // how fast H rows come out of L2 / Infinity Cache / HBM, not by arithmetic, so there is no MFMA use.
+#include <mutex>
+
 #include "common.hpp"
 
 namespace adaqp {
@@ -375,6 +377,10 @@ __global__ __launch_bounds__(kBlock) void spmm_carry_kernel(const SpmmArgs a)
     }
 }
 
+// Scratch of adaqp_spmm_csr_noalloc: one copy per GPU the library runs on, held until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress, never an address to pass to a kernel.
+static __device__ __align__(256) unsigned char scratch[ADAQP_SPMM_NOALLOC_SCRATCH_BYTES];
+
 // Geometry shared by the workspace query and the launch.
 struct Geometry { int32_t n_items; int64_t carry_ld; int64_t bytes; int64_t carry_off; };
 
@@ -529,4 +535,56 @@ extern "C" int adaqp_spmm_csr_packed(const int64_t *rowptr_dev, const int32_t *c
         ADAQP_HIP_TRY(err);
     }
     return ADAQP_OK;
+}
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];      // device address of `scratch` on each GPU, looked up once per GPU
+
+// Address of the current device's copy of `scratch`.  The first call on a device asks the runtime for it (which
+// may load the code object); later calls only read the table.
+int scratch_of_current_device(void **ptr_out)
+{
+    int dev = -1;
+    ADAQP_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ADAQP_ESIZE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        ADAQP_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return note_hip_error(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr_out = g_scratch_ptr[dev];
+    return ADAQP_OK;
+}
+
+}  // namespace
+
+extern "C" int adaqp_spmm_csr_noalloc(const int64_t *rowptr_dev, const int32_t *col_dev, const float *val_dev,
+                                      int64_t nnz, int64_t row_begin, int64_t row_end, int64_t nnz_range,
+                                      const float *H_dev, int64_t n_cols, int64_t ldh, int32_t dim,
+                                      float *out_dev, int64_t ldo, void *stream)
+{
+    // the same checks, in the same order, as adaqp_spmm_csr makes before it looks at its workspace
+    if (row_begin < 0 || row_end < row_begin || nnz < 0 || dim <= 0 || ldh < dim || ldo < dim || n_cols < 0)
+        return ADAQP_EINVAL;
+    const int64_t n_rows = row_end - row_begin;
+    if (n_rows == 0) return ADAQP_OK;
+    if (!rowptr_dev || !out_dev) return ADAQP_EINVAL;
+    if (nnz > 0 && (!col_dev || !val_dev || !H_dev || n_cols == 0)) return ADAQP_EINVAL;
+    if (n_rows > INT32_MAX - 1) return ADAQP_ESIZE;
+    if (!aligned_to(rowptr_dev, 8) || !aligned_to(col_dev, 4) || !aligned_to(val_dev, 4) ||
+        !aligned_to(H_dev, 4) || !aligned_to(out_dev, 4))
+        return ADAQP_EINVAL;
+    Geometry g;
+    if (!geometry(n_rows, (nnz_range < 0 || nnz_range > nnz) ? nnz : nnz_range, dim, &g)) return ADAQP_ESIZE;
+    if (g.bytes > (int64_t)ADAQP_SPMM_NOALLOC_SCRATCH_BYTES) return ADAQP_ESIZE;     // beyond the built-in scratch
+    void *ptr = nullptr;
+    const int rc = scratch_of_current_device(&ptr);
+    if (rc != ADAQP_OK) return rc;
+    return adaqp_spmm_csr(rowptr_dev, col_dev, val_dev, nnz, row_begin, row_end, nnz_range, H_dev, n_cols, ldh, dim,
+                          out_dev, ldo, ptr, (int64_t)ADAQP_SPMM_NOALLOC_SCRATCH_BYTES, stream);
 }
