@@ -27,6 +27,13 @@ namespace {
 // ---------------------------------------------------------------------------------------------------------
 struct Rand128 { uint32_t w0, w1, w2, w3; };
 
+// a ^ b ^ c in one instruction: gfx950's v_bitop3_b32 with the truth table of the three-input xor (the compiler
+// does not form it from two xors)
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 __device__ __forceinline__ Rand128 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                  uint32_t k0, uint32_t k1)
 {
@@ -36,9 +43,9 @@ __device__ __forceinline__ Rand128 philox4x32_10(uint32_t c0, uint32_t c1, uint3
     for (int r = 0; r < 10; ++r) {
         const uint64_t pA = (uint64_t)kMulA * c0;            // one v_mad_u64_u32 each
         const uint64_t pB = (uint64_t)kMulB * c2;
-        c0 = (uint32_t)(pB >> 32) ^ c1 ^ k0;
+        c0 = xor3((uint32_t)(pB >> 32), c1, k0);
         c1 = (uint32_t)pB;
-        c2 = (uint32_t)(pA >> 32) ^ c3 ^ k1;
+        c2 = xor3((uint32_t)(pA >> 32), c3, k1);
         c3 = (uint32_t)pA;
         k0 += kWeylA;
         k1 += kWeylB;
@@ -90,6 +97,19 @@ __device__ __forceinline__ void store_vec(float *p, const float *src)
     if constexpr (VW == 4) { *reinterpret_cast<V *>(p) = make_float4(src[0], src[1], src[2], src[3]); }
 }
 
+// Same, marked non-temporal.  For rows that are written once in whole 128-byte lines and not read back by the
+// kernel this is worth a quarter of the kernel's time on MI355X (measured: 19.7 -> 15.0 us for 30 000 rows of 602
+// columns, 29.7 -> 21.1 us for 120 000 rows of 256): the lines go out without being kept in the L2.
+template <int VW>
+__device__ __forceinline__ void store_vec_streaming(float *p, const float *src)
+{
+    typedef float vec_t __attribute__((ext_vector_type(VW)));
+    vec_t v;
+#pragma unroll
+    for (int k = 0; k < VW; ++k) v[k] = src[k];
+    __builtin_nontemporal_store(v, reinterpret_cast<vec_t *>(p));
+}
+
 // Codes of one granule (8 columns) at width B, merged little-endian into lo (and hi for B == 8).
 // The definition is trunc(min((x - Z) * inv, L) * 2^16).  With scale = inv * 2^16 and top = L * 2^16 the last
 // multiplication folds into the first: scaling by a power of two commutes with fp32 rounding, so
@@ -105,17 +125,20 @@ __device__ __forceinline__ void quantise_granule(const float (&x)[8], float Z, f
     const uint32_t words[4] = {rnd.w0, rnd.w1, rnd.w2, rnd.w3};
     lo = 0u;
     hi = 0u;
+    // Last column first: the code (bits 16 .. 16+B-1 of the sum) is moved to the top of its word and funnelled into
+    // the packed word from the right (v_alignbit_b32: shift, extract and merge in one instruction), so column 0
+    // ends up in the lowest bits.
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
+    for (int k = 7; k >= 0; --k) {
         float pos = (x[k] - Z) * scale;                       // Eq. 4 argument (in 16.16 fixed point), >= 0
         pos = fminf(pos, top);                                // the top element may overshoot by an ulp
         if (TWO_STEP) pos = pos * 65536.0f;
         const uint32_t fixed = (uint32_t)pos;                 // truncated
         const uint32_t r16 = (k & 1) ? (words[k >> 1] >> 16) : (words[k >> 1] & 0xFFFFu);
-        uint32_t code = (fixed + r16) >> 16;                  // App. A.1: up with probability frac
-        if (MASK) code = (col0 + k < dim) ? code : 0u;        // padding bits are zero
-        if (B * k < 32) lo |= code << ((B * k) & 31);
-        else            hi |= code << ((B * k) & 31);
+        uint32_t sum = (fixed + r16) << (16 - B);             // App. A.1: up with probability frac; code = top B bits
+        if (MASK) sum = (col0 + k < dim) ? sum : 0u;          // padding bits are zero
+        if (B * k < 32) lo = __builtin_amdgcn_alignbit(lo, sum, 32 - B);
+        else            hi = __builtin_amdgcn_alignbit(hi, sum, 32 - B);
     }
 }
 
@@ -208,10 +231,10 @@ __device__ __forceinline__ void pin(Rand128 &r)
 
 // ---------------------------------------------------------------------------------------------------------
 // Register-resident rows: GPL granules per lane, LPR = 2^lpr_log2 lanes per row, 64/LPR rows per wave.
-// Order of work inside a wave: (1) issue the loads of the slots' index entries; (2) while they are in
-// flight, run Philox for the first granules - the rounding values depend only on (seed, slot, column), not
-// on memory; (3) issue all row loads; (4) Philox for the remaining granules while the rows stream in;
-// (5) min / max, scale, codes, stores.
+// Order of work inside a wave: (1) issue the loads of the slots' index entries; (2) with four or more granules
+// per lane, run Philox for the first two while those are in flight - the rounding values depend only on (seed,
+// slot, column), not on memory; (3) issue all row loads; (4) Philox for the remaining granules while the rows
+// stream in; (5) min / max, scale, codes, stores.
 // ---------------------------------------------------------------------------------------------------------
 template <int GPL, int VW>
 __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a)
@@ -232,7 +255,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
 
     // (2) rounding values of the lane's first granules (the barriers and pins keep the compiler from sinking
     // the arithmetic behind the wait for the rows)
-    constexpr int kEarly = GPL < 2 ? GPL : 2;
+    constexpr int kEarly = GPL <= 3 ? 0 : 2;     // light waves: the row loads go out first, the generator runs under them
     Rand128 rnd[GPL];
     const uint32_t s_lo = (uint32_t)s, s_hi = (uint32_t)((uint64_t)s >> 32);
 #pragma unroll
@@ -376,9 +399,9 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_wide_kernel(const QuantA
 // ---------------------------------------------------------------------------------------------------------
 // Receive side.  A lane turns VW consecutive codes into VW floats and stores them as one vector, so a wave
 // writes 64*VW*4 contiguous bytes per step; VW*b divides 32, so the codes of one vector never straddle a
-// 32-bit word of the packed row.  A wave owns R consecutive slots: lanes 0..R-1 fetch the R slots' index
-// entries in one go, then all R*NV packed words are requested before the first one is decoded, so a wave
-// pays two memory latencies for R rows.
+// 32-bit word of the packed row.  A wave owns R consecutive slots, R chosen so that it writes about 4 KB (light
+// waves stream best here): their index entries are fetched in one go, then all R*NV packed words are requested
+// before the first one is decoded, so a wave pays two memory latencies for R rows.
 // ---------------------------------------------------------------------------------------------------------
 struct DequantArgs {
     const uint8_t *packed;
@@ -401,36 +424,76 @@ __device__ __forceinline__ int64_t readlane_i64(int64_t v, int lane_id)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-template <int VW, int NV, int R>
+// SCALAR: the wave's slot numbers are wave-uniform, so the index entries of its R slots can come through the scalar
+// cache (R <= 2); otherwise lanes 0..R-1 fetch them with one vector load each and broadcast them (R = 4).
+// STREAM: rows are written in whole lines (line-padded layout): non-temporal stores.
+template <int VW, int NV, int R, bool SCALAR, bool STREAM>
 __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(const DequantArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t t0 = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * R;      // wave-uniform
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t t0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * R;                    // wave-uniform
     if (t0 >= a.n_recv) return;
 
-    // lane k < R: index entries of the slot at position t0 + k
-    int64_t t_mine = t0 + lane < a.n_recv ? t0 + lane : a.n_recv - 1;
-    int32_t my_r = -1, my_b = 0;
-    int64_t my_off = 0;
-    float my_z = 0.0f, my_s = 0.0f;
-    if (lane < R) {
-        bool in_list = true;
-        if (a.order) {
-            const int32_t o = a.order[t_mine];
-            in_list = o >= 0 && o < a.n_recv;
-            t_mine = in_list ? o : 0;
+    int32_t r_of[R], b_of[R];
+    int64_t off_of[R];
+    float z_of[R], s_of[R];
+    if (SCALAR) {
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            int64_t t = t0 + k < a.n_recv ? t0 + k : a.n_recv - 1;
+            bool in_list = t0 + k < a.n_recv;
+            if (a.order) {
+                const int32_t o = a.order[t];
+                in_list = in_list && o >= 0 && o < a.n_recv;
+                t = in_list ? o : 0;
+            }
+            const int32_t r = a.halo_idx[t];
+            const int32_t b = a.bits[t];
+            const int64_t off = a.row_offset[t];
+            const float2 zs = *reinterpret_cast<const float2 *>(a.params + 2 * t);
+            const int64_t stride = 4 * (((int64_t)a.dim * b + 31) >> 5);
+            const bool ok = in_list && r >= 0 && r < a.n_feat_rows && (b == 2 || b == 4 || b == 8) && off >= 0 &&
+                            (off & 3) == 0 && off + stride <= a.packed_bytes;
+            r_of[k] = ok ? r : -1;
+            b_of[k] = b;
+            off_of[k] = off;
+            z_of[k] = zs.x;
+            s_of[k] = zs.y;
         }
-        my_r = a.halo_idx[t_mine];
-        my_b = a.bits[t_mine];
-        my_off = a.row_offset[t_mine];
-        const float2 zs = *reinterpret_cast<const float2 *>(a.params + 2 * t_mine);
-        my_z = zs.x;
-        my_s = zs.y;
-        const int64_t stride = 4 * (((int64_t)a.dim * my_b + 31) >> 5);
-        const bool ok = in_list && t0 + lane < a.n_recv && my_r >= 0 && my_r < a.n_feat_rows &&
-                        (my_b == 2 || my_b == 4 || my_b == 8) && my_off >= 0 && (my_off & 3) == 0 &&
-                        my_off + stride <= a.packed_bytes;
-        if (!ok) my_r = -1;
+    } else {
+        // lane k < R: index entries of the slot at position t0 + k
+        int64_t t_mine = t0 + lane < a.n_recv ? t0 + lane : a.n_recv - 1;
+        int32_t my_r = -1, my_b = 0;
+        int64_t my_off = 0;
+        float my_z = 0.0f, my_s = 0.0f;
+        if (lane < R) {
+            bool in_list = true;
+            if (a.order) {
+                const int32_t o = a.order[t_mine];
+                in_list = o >= 0 && o < a.n_recv;
+                t_mine = in_list ? o : 0;
+            }
+            my_r = a.halo_idx[t_mine];
+            my_b = a.bits[t_mine];
+            my_off = a.row_offset[t_mine];
+            const float2 zs = *reinterpret_cast<const float2 *>(a.params + 2 * t_mine);
+            my_z = zs.x;
+            my_s = zs.y;
+            const int64_t stride = 4 * (((int64_t)a.dim * my_b + 31) >> 5);
+            const bool ok = in_list && t0 + lane < a.n_recv && my_r >= 0 && my_r < a.n_feat_rows &&
+                            (my_b == 2 || my_b == 4 || my_b == 8) && my_off >= 0 && (my_off & 3) == 0 &&
+                            my_off + stride <= a.packed_bytes;
+            if (!ok) my_r = -1;
+        }
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            r_of[k] = __builtin_amdgcn_readlane(my_r, k);
+            b_of[k] = __builtin_amdgcn_readlane(my_b, k);
+            off_of[k] = readlane_i64(my_off, k);
+            z_of[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_z), k));
+            s_of[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_s), k));
+        }
     }
 
     const bool last_ok = ((NV - 1) * kWave + lane) * VW < a.write_dim;
@@ -438,13 +501,10 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(const DequantArg
     // past the row re-reads the row's last word, a skipped slot reads the buffer's first word) so that they
     // form one straight run of instructions with a single wait behind it.
     uint32_t w[R][NV];
-    int32_t b_of[R];
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-        const int32_t r = __builtin_amdgcn_readlane(my_r, k);
-        b_of[k] = __builtin_amdgcn_readlane(my_b, k);
-        const int64_t off = readlane_i64(my_off, k);
-        const uint32_t *words = reinterpret_cast<const uint32_t *>(a.packed + (r >= 0 ? off : 0));
+        const int32_t r = r_of[k];
+        const uint32_t *words = reinterpret_cast<const uint32_t *>(a.packed + (r >= 0 ? off_of[k] : 0));
         const uint32_t last_word = r >= 0 ? (uint32_t)(((int64_t)a.dim * b_of[k] - 1) >> 5) : 0u;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
@@ -455,10 +515,9 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(const DequantArg
     }
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-        const int32_t r = __builtin_amdgcn_readlane(my_r, k);
+        const int32_t r = r_of[k];
         if (r < 0) continue;
-        const float Z = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_z), k));
-        const float S = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_s), k));
+        const float Z = z_of[k], S = s_of[k];
         const int32_t b = b_of[k];
         const uint32_t mask = (1u << b) - 1u;
         float *h = a.feat + (int64_t)r * a.ld;
@@ -475,7 +534,8 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(const DequantArg
                     y[q] = scaled + Z;
                     if (v == NV - 1 && (v * kWave + lane) * VW + q >= a.dim) y[q] = 0.0f;   // row padding
                 }
-                store_vec<VW>(h + (v * kWave + lane) * VW, y);
+                if (STREAM) store_vec_streaming<VW>(h + (v * kWave + lane) * VW, y);
+                else        store_vec<VW>(h + (v * kWave + lane) * VW, y);
             }
         }
     }
@@ -543,7 +603,7 @@ struct DequantAddArgs {
 };
 
 // One destination segment g, worked on by a whole wave.
-template <int VW, int NV>       // NV: vectors per lane and column chunk
+template <int VW, int NV, bool STREAM>       // NV: vectors per lane and column chunk; STREAM: non-temporal row stores
 __device__ void add_one_segment(const DequantAddArgs &a, int64_t g, int lane)
 {
     constexpr int G = 4;        // slots whose packed words are requested together
@@ -634,25 +694,28 @@ __device__ void add_one_segment(const DequantAddArgs &a, int64_t g, int lane)
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int32_t c = c0 + (v * kWave + lane) * VW;
-            if (c < a.dim) store_vec<VW>(row + c, acc[v]);
+            if (c < a.dim) {
+                if (STREAM) store_vec_streaming<VW>(row + c, acc[v]);
+                else        store_vec<VW>(row + c, acc[v]);
+            }
         }
     }
 }
 
-template <int VW, int NV>
+template <int VW, int NV, bool STREAM>
 __global__ __launch_bounds__(kBlock) void unpack_dequant_add_kernel(const DequantAddArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t g = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);             // wave-uniform
     if (g >= a.n_seg) return;
-    add_one_segment<VW, NV>(a, g, lane);
+    add_one_segment<VW, NV, STREAM>(a, g, lane);
 }
 
 // Rows of at most two vectors per lane: a wave takes S = 4 consecutive segments at once.  Most destination rows
 // hear from one or two peers, so a wave per row spends its life waiting on a chain of dependent loads (segment
 // bounds -> slot numbers -> index entries -> row and packed words); here the chain is walked once for S rows,
 // and their row loads and packed words are all in flight together.  Same arithmetic and order per row as above.
-template <int VW, int NV, int S>
+template <int VW, int NV, int S, bool STREAM>
 __global__ __launch_bounds__(kBlock) void unpack_dequant_add4_kernel(const DequantAddArgs a)
 {
     constexpr int G = 4;
@@ -678,7 +741,7 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_add4_kernel(const Dequa
     const int64_t total = sp[S] - sp[0];
     if (total <= 0) return;
     if (total > kWave) {                                    // a crowd on one of the rows: one segment at a time
-        for (int i = 0; i < ns; ++i) add_one_segment<VW, NV>(a, g0 + i, lane);
+        for (int i = 0; i < ns; ++i) add_one_segment<VW, NV, STREAM>(a, g0 + i, lane);
         return;
     }
     const int n_win = (int)total;
@@ -777,7 +840,10 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_add4_kernel(const Dequa
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int32_t c = (v * kWave + lane) * VW;
-            if (c < a.dim) store_vec<VW>(a.grad + (int64_t)r[i] * a.ld + c, acc[i][v]);
+            if (c < a.dim) {
+                if (STREAM) store_vec_streaming<VW>(a.grad + (int64_t)r[i] * a.ld + c, acc[i][v]);
+                else        store_vec<VW>(a.grad + (int64_t)r[i] * a.ld + c, acc[i][v]);
+            }
         }
     }
 }
@@ -809,16 +875,21 @@ hipError_t launch_quantize(const QuantArgs &a, int gpl, dim3 grid, hipStream_t s
     return hipGetLastError();
 }
 
-constexpr int kDequantRows = 4;      // slots per wave on the receive side
 constexpr int kMaxDequantNv = 8;
 
-template <int VW, int R>
-hipError_t launch_dequant(const DequantArgs &a, int nv, dim3 grid, hipStream_t st)
+// Slots per wave on the receive side: four rows of one vector per lane, two of two, else one (measured on 256-,
+// 300- and 602-column rows: 21.1 / 19.5 / 14.4 us against 25.4 / 21.1 / 15.0 us for the next best choice).
+inline int dequant_rows_per_wave(int nv) { return nv == 1 ? 4 : (nv == 2 ? 2 : 1); }
+
+template <int VW, bool STREAM>
+hipError_t launch_dequant(const DequantArgs &a, int nv, int64_t n_waves, hipStream_t st)
 {
+    const dim3 grid((unsigned)((n_waves + kWavesPerBlock - 1) / kWavesPerBlock));
     switch (nv) {
-#define ADAQP_CASE(N) case N: hipLaunchKernelGGL((unpack_dequant_kernel<VW, N, R>), grid, dim3(kBlock), 0, st, a); break;
-        ADAQP_CASE(1) ADAQP_CASE(2) ADAQP_CASE(3) ADAQP_CASE(4)
-        ADAQP_CASE(5) ADAQP_CASE(6) ADAQP_CASE(7) ADAQP_CASE(8)
+        case 1: hipLaunchKernelGGL((unpack_dequant_kernel<VW, 1, 4, false, STREAM>), grid, dim3(kBlock), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((unpack_dequant_kernel<VW, 2, 2, true, STREAM>), grid, dim3(kBlock), 0, st, a); break;
+#define ADAQP_CASE(N) case N: hipLaunchKernelGGL((unpack_dequant_kernel<VW, N, 1, true, STREAM>), grid, dim3(kBlock), 0, st, a); break;
+        ADAQP_CASE(3) ADAQP_CASE(4) ADAQP_CASE(5) ADAQP_CASE(6) ADAQP_CASE(7) ADAQP_CASE(8)
 #undef ADAQP_CASE
         default: return hipErrorInvalidValue;
     }
@@ -877,19 +948,36 @@ extern "C" int adaqp_quantize_pack_trace(const float *feat_dev, int64_t n_feat_r
     a.lpr_log2 = 0;
     hipStream_t st = (hipStream_t)stream;
 
-    // lanes per row / granules per lane: least padding first, then the count closest to four granules
+    // Lanes per row / granules per lane.  Light waves do best (measured on c1-c4-shaped inputs: a wave that carries 2-5
+    // KB of rows beats one that carries 8-10 KB by 3-6 %): two or three granules per lane if that leaves at most a
+    // quarter of the lanes' granule slots idle (602 columns -> 32 x 3, 300 -> 16 x 3, 256 -> 16 x 2, 128 -> 8 x 2);
+    // otherwise least padding first, then the count closest to four granules.
     int best_k = -1, best_gpl = 0;
     int64_t best_waste = INT64_MAX;
     for (int k = 0; k <= 6; ++k) {
         const int lpr = 1 << k;
         const int gpl = (a.n_granules + lpr - 1) / lpr;
-        if (gpl > kMaxGpl) continue;
+        if (gpl > 3 || gpl < 2) continue;
         const int64_t waste = (int64_t)lpr * gpl - a.n_granules;
-        const bool closer = (gpl > 4 ? gpl - 4 : 4 - gpl) < (best_gpl > 4 ? best_gpl - 4 : 4 - best_gpl);
-        if (waste < best_waste || (waste == best_waste && closer)) {
+        if (4 * waste > (int64_t)lpr * gpl) continue;
+        if (waste < best_waste || (waste == best_waste && gpl > best_gpl)) {
             best_waste = waste;
             best_k = k;
             best_gpl = gpl;
+        }
+    }
+    if (best_k < 0) {
+        for (int k = 0; k <= 6; ++k) {
+            const int lpr = 1 << k;
+            const int gpl = (a.n_granules + lpr - 1) / lpr;
+            if (gpl > kMaxGpl) continue;
+            const int64_t waste = (int64_t)lpr * gpl - a.n_granules;
+            const bool closer = (gpl > 4 ? gpl - 4 : 4 - gpl) < (best_gpl > 4 ? best_gpl - 4 : 4 - best_gpl);
+            if (waste < best_waste || (waste == best_waste && closer)) {
+                best_waste = waste;
+                best_k = k;
+                best_gpl = gpl;
+            }
         }
     }
     if (best_k < 0) {
@@ -954,12 +1042,18 @@ extern "C" int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_by
     const int nv = (write_dim + kWave * vw - 1) / (kWave * vw);
     if (nv <= kMaxDequantNv) {
         a.write_dim = write_dim;
-        const int64_t waves = (n_recv + kDequantRows - 1) / kDequantRows;
-        const dim3 grid((unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock));
+        const int rows = dequant_rows_per_wave(nv);
+        const int64_t waves = (n_recv + rows - 1) / rows;
         hipError_t err;
-        if (vw == 4) err = launch_dequant<4, kDequantRows>(a, nv, grid, st);
-        else if (vw == 2) err = launch_dequant<2, kDequantRows>(a, nv, grid, st);
-        else err = launch_dequant<1, kDequantRows>(a, nv, grid, st);
+        // whole-line writes go out as non-temporal stores; rows that share lines with their neighbours stay with
+        // ordinary stores, which the L2 merges
+        if (whole_lines) {
+            err = launch_dequant<4, true>(a, nv, waves, st);            // line-padded rows take 16-byte vectors
+        } else {
+            if (vw == 4) err = launch_dequant<4, false>(a, nv, waves, st);
+            else if (vw == 2) err = launch_dequant<2, false>(a, nv, waves, st);
+            else err = launch_dequant<1, false>(a, nv, waves, st);
+        }
         ADAQP_HIP_TRY(err);
         return ADAQP_OK;
     }
@@ -1015,16 +1109,19 @@ extern "C" int adaqp_unpack_dequant_add(const uint8_t *packed_dev, int64_t packe
     const int nv = (dim + kWave * vw - 1) / (kWave * vw);          // rows wider than 4 vectors per lane: chunks of 4
     const int seg_per_wave = 4;                 // eight per wave measured slower (63 against 58 us on 150 000 messages)
     const dim3 grid4((unsigned)((n_seg + seg_per_wave * kWavesPerBlock - 1) / (seg_per_wave * kWavesPerBlock)));
-#define ADAQP_ADD(VW_)                                                                                             \
+#define ADAQP_ADD(VW_, ST_)                                                                                        \
     do {                                                                                                           \
-        if (nv == 1) hipLaunchKernelGGL((unpack_dequant_add4_kernel<VW_, 1, 4>), grid4, dim3(kBlock), 0, st, a);   \
-        else if (nv == 2) hipLaunchKernelGGL((unpack_dequant_add4_kernel<VW_, 2, 4>), grid4, dim3(kBlock), 0, st, a); \
-        else if (nv == 3) hipLaunchKernelGGL((unpack_dequant_add_kernel<VW_, 3>), grid, dim3(kBlock), 0, st, a);   \
-        else hipLaunchKernelGGL((unpack_dequant_add_kernel<VW_, 4>), grid, dim3(kBlock), 0, st, a);                \
+        if (nv == 1) hipLaunchKernelGGL((unpack_dequant_add4_kernel<VW_, 1, 4, ST_>), grid4, dim3(kBlock), 0, st, a);   \
+        else if (nv == 2) hipLaunchKernelGGL((unpack_dequant_add4_kernel<VW_, 2, 4, ST_>), grid4, dim3(kBlock), 0, st, a); \
+        else if (nv == 3) hipLaunchKernelGGL((unpack_dequant_add_kernel<VW_, 3, ST_>), grid, dim3(kBlock), 0, st, a);   \
+        else hipLaunchKernelGGL((unpack_dequant_add_kernel<VW_, 4, ST_>), grid, dim3(kBlock), 0, st, a);                \
     } while (0)
-    if (vw == 4) ADAQP_ADD(4);
-    else if (vw == 2) ADAQP_ADD(2);
-    else ADAQP_ADD(1);
+    // rows that are whole 128-byte lines (line-padded layout, dim a multiple of 32) are written back non-temporally
+    const bool whole_lines = line_padded(grad_dev, ld) && dim % 32 == 0;
+    if (vw == 4 && whole_lines) ADAQP_ADD(4, true);
+    else if (vw == 4) ADAQP_ADD(4, false);
+    else if (vw == 2) ADAQP_ADD(2, false);
+    else ADAQP_ADD(1, false);
 #undef ADAQP_ADD
     ADAQP_HIP_TRY(hipGetLastError());
     return ADAQP_OK;
