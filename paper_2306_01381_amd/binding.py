@@ -106,6 +106,8 @@ _SIGNATURES = {
     "adaqp_spmm_csr_packed": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _i64, _i64, _i32,
                                              _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "adaqp_layer_step": (ctypes.c_int, [ctypes.POINTER(LayerDesc)]),
+    "adaqp_probe_quantize_pack": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _vp, _i64, _vp, _vp]),
+    "adaqp_probe_stream": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp]),
     "adaqp_layer_desc_bytes": (_i64, []),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -474,3 +476,28 @@ def adaqp_spmm_csr_packed(rowptr: torch.Tensor, col: torch.Tensor, val: torch.Te
 
 def adaqp_layer_step(desc: LayerDesc) -> None:
     _check(lib().adaqp_layer_step(ctypes.byref(desc)), "adaqp_layer_step")
+
+
+def adaqp_probe_quantize_pack(feat: torch.Tensor, dim: int, send_idx: torch.Tensor, bits: torch.Tensor,
+                              row_offset: torch.Tensor, packed: torch.Tensor, params: torch.Tensor,
+                              stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Measurement aid (include/adaqp_probe.h): the no-compute twin of adaqp_quantize_pack."""
+    fp, n_rows, ld = _matrix(feat, "feat")
+    _check(lib().adaqp_probe_quantize_pack(fp, n_rows, ld, dim, _dev(send_idx, torch.int32, "send_idx"),
+                                           _dev(bits, torch.uint8, "bits"),
+                                           _dev(row_offset, torch.int64, "row_offset"), send_idx.shape[0],
+                                           _dev(packed, torch.uint8, "packed"), packed.numel(),
+                                           _dev(params, torch.float32, "params"), _stream(stream)),
+           "adaqp_probe_quantize_pack")
+
+
+def adaqp_probe_stream(src: torch.Tensor, dst: torch.Tensor, nbytes: int, write_side: bool,
+                       stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Measurement aid (include/adaqp_probe.h): a plain stream over nbytes bytes of src (read side) or dst."""
+    big, small = (dst, src) if write_side else (src, dst)
+    if big.numel() * big.element_size() < nbytes or small.numel() * small.element_size() < nbytes // 8 + 4096:
+        raise ValueError("adaqp_probe_stream: a buffer is smaller than the stream")
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise TypeError("adaqp_probe_stream needs contiguous device tensors")
+    _check(lib().adaqp_probe_stream(src.data_ptr(), dst.data_ptr(), nbytes, 1 if write_side else 0, _stream(stream)),
+           "adaqp_probe_stream")

@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libadaqp.so")
-SOURCES = ["codec.hip", "spmm.hip", "layer.hip", "assign.hip", "spmm_tiled.hip", "spmm_panels.hip"]
+SOURCES = ["codec.hip", "spmm.hip", "layer.hip", "assign.hip", "spmm_tiled.hip", "spmm_panels.hip", "probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -ffp-contract=off: the integer codes depend on every fp32 rounding, so nothing may be fused behind our back.

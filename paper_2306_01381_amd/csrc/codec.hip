@@ -18,6 +18,7 @@
 // fp32 arithmetic is written operation by operation and the file is compiled with -ffp-contract=off: the
 // integer codes depend on every rounding.
 #include "common.hpp"
+#include "adaqp_probe.h"
 
 namespace adaqp {
 namespace {
@@ -236,7 +237,10 @@ __device__ __forceinline__ void pin(Rand128 &r)
 // slot, column), not on memory; (3) issue all row loads; (4) Philox for the remaining granules while the rows
 // stream in; (5) min / max, scale, codes, stores.
 // ---------------------------------------------------------------------------------------------------------
-template <int GPL, int VW>
+// PROBE: the measurement twin - the same grid, index loads, row loads and stores (same instructions, same
+// addresses), but no generator, no min / max reduction, no codes: what is stored is derived from the loaded values
+// with two operations per granule.  Its time is the floor of this access pattern.
+template <int GPL, int VW, bool PROBE>
 __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -255,7 +259,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
 
     // (2) rounding values of the lane's first granules (the barriers and pins keep the compiler from sinking
     // the arithmetic behind the wait for the rows)
-    constexpr int kEarly = GPL <= 3 ? 0 : 2;     // light waves: the row loads go out first, the generator runs under them
+    constexpr int kEarly = (PROBE || GPL <= 3) ? 0 : 2;  // light waves: the row loads go out first, the generator runs under them
     Rand128 rnd[GPL];
     const uint32_t s_lo = (uint32_t)s, s_hi = (uint32_t)((uint64_t)s >> 32);
 #pragma unroll
@@ -286,6 +290,24 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(const QuantArgs a
         }
     }
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (PROBE) {
+        float m = x[0][0];
+#pragma unroll
+        for (int i = 0; i < GPL; ++i) m = fmaxf(m, x[i][3]);
+        if (valid && l == 0) *reinterpret_cast<float2 *>(a.params + 2 * s) = make_float2(m, m);
+        uint8_t *prow = a.packed + (valid ? off : 0);
+#pragma unroll
+        for (int i = 0; i < GPL; ++i) {
+            const int32_t g = i * lpr + l;
+            const uint32_t word = __builtin_bit_cast(uint32_t, x[i][0]) ^ __builtin_bit_cast(uint32_t, x[i][5]);
+            if (valid && g < a.n_granules) {
+                if (b == 4)      store_granule<4>(prow, g, a.n_granules, stride, word, word);
+                else if (b == 2) store_granule<2>(prow, g, a.n_granules, stride, word, word);
+                else             store_granule<8>(prow, g, a.n_granules, stride, word, word);
+            }
+        }
+        return;
+    }
     // (4)
 #pragma unroll
     for (int i = kEarly; i < GPL; ++i) {
@@ -862,11 +884,11 @@ int vector_width(const void *base, int64_t ld, int32_t dim, bool whole_vectors)
 // Rows start on 128-byte lines and the pitch is a whole number of lines: the layout this library is built for.
 bool line_padded(const void *base, int64_t ld) { return ld % 32 == 0 && aligned_to(base, 128); }
 
-template <int VW>
+template <int VW, bool PROBE = false>
 hipError_t launch_quantize(const QuantArgs &a, int gpl, dim3 grid, hipStream_t st)
 {
     switch (gpl) {
-#define ADAQP_CASE(G) case G: hipLaunchKernelGGL((quantize_pack_kernel<G, VW>), grid, dim3(kBlock), 0, st, a); break;
+#define ADAQP_CASE(G) case G: hipLaunchKernelGGL((quantize_pack_kernel<G, VW, PROBE>), grid, dim3(kBlock), 0, st, a); break;
         ADAQP_CASE(1) ADAQP_CASE(2) ADAQP_CASE(3) ADAQP_CASE(4)
         ADAQP_CASE(5) ADAQP_CASE(6) ADAQP_CASE(7) ADAQP_CASE(8)
 #undef ADAQP_CASE
@@ -910,11 +932,13 @@ extern "C" int adaqp_quantize_pack(const float *feat_dev, int64_t n_feat_rows, i
                                      seed, packed_dev, packed_bytes, params_dev, nullptr, nullptr, stream);
 }
 
-extern "C" int adaqp_quantize_pack_trace(const float *feat_dev, int64_t n_feat_rows, int64_t ld, int32_t dim,
-                                         const int32_t *send_idx_dev, const uint8_t *bits_dev,
-                                         const int64_t *row_offset_dev, int64_t n_send, uint64_t seed,
-                                         uint8_t *packed_dev, int64_t packed_bytes, float *params_dev,
-                                         const float *alpha_sq_dev, float *beta_dev, void *stream)
+namespace {
+
+// Argument checks, launch shape and launch of the send side; `probe` launches the measurement twin of the kernel.
+int quantize_pack_launch(const float *feat_dev, int64_t n_feat_rows, int64_t ld, int32_t dim,
+                         const int32_t *send_idx_dev, const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                         int64_t n_send, uint64_t seed, uint8_t *packed_dev, int64_t packed_bytes, float *params_dev,
+                         const float *alpha_sq_dev, float *beta_dev, void *stream, bool probe)
 {
     if ((alpha_sq_dev == nullptr) != (beta_dev == nullptr)) return ADAQP_EINVAL;
     if (!aligned_to(alpha_sq_dev, 4) || !aligned_to(beta_dev, 4)) return ADAQP_EINVAL;
@@ -981,6 +1005,7 @@ extern "C" int adaqp_quantize_pack_trace(const float *feat_dev, int64_t n_feat_r
         }
     }
     if (best_k < 0) {
+        if (probe) return ADAQP_EINVAL;                 // rows too wide for registers have no twin
         const int64_t blocks = (n_send + kWavesPerBlock - 1) / kWavesPerBlock;
         if (blocks > INT32_MAX) return ADAQP_ESIZE;
         hipLaunchKernelGGL(quantize_pack_wide_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
@@ -994,11 +1019,35 @@ extern "C" int adaqp_quantize_pack_trace(const float *feat_dev, int64_t n_feat_r
     const dim3 grid((unsigned)blocks);
     const int vw = vector_width(feat_dev, ld, dim, false);
     hipError_t err;
-    if (vw == 4) err = launch_quantize<4>(a, best_gpl, grid, st);
+    if (probe) {
+        if (vw != 4) return ADAQP_EINVAL;               // the twin exists for 16-byte-aligned rows only
+        err = launch_quantize<4, true>(a, best_gpl, grid, st);
+    } else if (vw == 4) err = launch_quantize<4>(a, best_gpl, grid, st);
     else if (vw == 2) err = launch_quantize<2>(a, best_gpl, grid, st);
     else err = launch_quantize<1>(a, best_gpl, grid, st);
     ADAQP_HIP_TRY(err);
     return ADAQP_OK;
+}
+
+}  // namespace
+
+extern "C" int adaqp_quantize_pack_trace(const float *feat_dev, int64_t n_feat_rows, int64_t ld, int32_t dim,
+                                         const int32_t *send_idx_dev, const uint8_t *bits_dev,
+                                         const int64_t *row_offset_dev, int64_t n_send, uint64_t seed,
+                                         uint8_t *packed_dev, int64_t packed_bytes, float *params_dev,
+                                         const float *alpha_sq_dev, float *beta_dev, void *stream)
+{
+    return quantize_pack_launch(feat_dev, n_feat_rows, ld, dim, send_idx_dev, bits_dev, row_offset_dev, n_send, seed,
+                                packed_dev, packed_bytes, params_dev, alpha_sq_dev, beta_dev, stream, false);
+}
+
+extern "C" int adaqp_probe_quantize_pack(const float *feat_dev, int64_t n_feat_rows, int64_t ld, int32_t dim,
+                                         const int32_t *send_idx_dev, const uint8_t *bits_dev,
+                                         const int64_t *row_offset_dev, int64_t n_send,
+                                         uint8_t *packed_dev, int64_t packed_bytes, float *params_dev, void *stream)
+{
+    return quantize_pack_launch(feat_dev, n_feat_rows, ld, dim, send_idx_dev, bits_dev, row_offset_dev, n_send, 0,
+                                packed_dev, packed_bytes, params_dev, nullptr, nullptr, stream, true);
 }
 
 extern "C" int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
