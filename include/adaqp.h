@@ -456,7 +456,12 @@ typedef struct adaqp_layer_desc {
 
 /* Enqueues one layer step.  On return all work has been enqueued and stream_msg has been made to wait for
  * stream_agg, so synchronising stream_msg completes the step.  The three schedules give bit-identical
- * results.  Errors: EINVAL, ESIZE, EHIP. */
+ * results.
+ * ISOLATED and FREE only overlap anything if stream_msg and stream_agg sit on different hardware queues.  HIP maps
+ * the streams of a process onto a few hardware queues (four by default): in a process that has created more
+ * streams than that, the two may share a queue, and the step then takes the SERIAL time (same results).  A caller
+ * that depends on the overlap creates these two streams first, or times the step against SERIAL once.
+ * Errors: EINVAL, ESIZE, EHIP. */
 int adaqp_layer_step(const adaqp_layer_desc *desc_host);
 
 /* sizeof(adaqp_layer_desc) as this library was built: lets a binding in another language check its mirror of the

@@ -38,6 +38,15 @@ int adaqp_probe_quantize_pack(const float *feat_dev, int64_t n_feat_rows, int64_
  * Errors: EINVAL (null, alignment, negative size), ESIZE (more than 2^40 bytes), EHIP. */
 int adaqp_probe_stream(const void *src_dev, void *dst_dev, int64_t bytes, int32_t write_side, void *stream);
 
+/* Launches a 1-D grid of n_workgroups workgroups (256 threads, as every kernel of the library) and records the XCD
+ * each one runs on: xcd_out_dev[i] = XCC_ID of workgroup i.  adaqp_spmm_csr_tiled and adaqp_spmm_csr_panels pin
+ * column range i mod ADAQP_SPMM_TILES of the graph to workgroup i, which keeps one range per L2 only if the
+ * hardware deals consecutive workgroups of a grid to consecutive XCDs; this call lets a test or a benchmark check
+ * that on the GPU at hand (on an idle MI355X: xcd[i] - xcd[0] = i mod 8).  If the mapping were different the two
+ * kernels would still be correct, only slower.
+ * Errors: EINVAL, EHIP. */
+int adaqp_probe_xcd_of_workgroup(int32_t *xcd_out_dev, int32_t n_workgroups, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

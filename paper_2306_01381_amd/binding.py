@@ -108,6 +108,7 @@ _SIGNATURES = {
     "adaqp_layer_step": (ctypes.c_int, [ctypes.POINTER(LayerDesc)]),
     "adaqp_probe_quantize_pack": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _vp, _i64, _vp, _vp]),
     "adaqp_probe_stream": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp]),
+    "adaqp_probe_xcd_of_workgroup": (ctypes.c_int, [_vp, _i32, _vp]),
     "adaqp_layer_desc_bytes": (_i64, []),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -501,3 +502,12 @@ def adaqp_probe_stream(src: torch.Tensor, dst: torch.Tensor, nbytes: int, write_
         raise TypeError("adaqp_probe_stream needs contiguous device tensors")
     _check(lib().adaqp_probe_stream(src.data_ptr(), dst.data_ptr(), nbytes, 1 if write_side else 0, _stream(stream)),
            "adaqp_probe_stream")
+
+
+def adaqp_probe_xcd_of_workgroup(n_workgroups: int, device="cuda:0",
+                                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Measurement aid (include/adaqp_probe.h): the XCD each workgroup of a 1-D grid runs on (int32 device tensor)."""
+    out = torch.full((max(n_workgroups, 1),), -1, dtype=torch.int32, device=device)
+    _check(lib().adaqp_probe_xcd_of_workgroup(out.data_ptr(), n_workgroups, _stream(stream)),
+           "adaqp_probe_xcd_of_workgroup")
+    return out[:n_workgroups]

@@ -48,10 +48,29 @@ __global__ __launch_bounds__(kBlock) void stream_write_kernel(const uint32_t *sr
     }
 }
 
+// Which XCD each workgroup of a 1-D grid runs on (hardware register XCC_ID).
+__global__ __launch_bounds__(kBlock) void xcd_of_workgroup_kernel(int32_t *out, int32_t n)
+{
+    uint32_t xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    if (threadIdx.x == 0 && (int32_t)blockIdx.x < n) out[blockIdx.x] = (int32_t)(xcc & 0xF);
+}
+
 }  // namespace
 }  // namespace adaqp
 
 using namespace adaqp;
+
+extern "C" int adaqp_probe_xcd_of_workgroup(int32_t *xcd_out_dev, int32_t n_workgroups, void *stream)
+{
+    if (n_workgroups < 0) return ADAQP_EINVAL;
+    if (n_workgroups == 0) return ADAQP_OK;
+    if (!xcd_out_dev || !aligned_to(xcd_out_dev, 4)) return ADAQP_EINVAL;
+    hipLaunchKernelGGL(xcd_of_workgroup_kernel, dim3((unsigned)n_workgroups), dim3(kBlock), 0, (hipStream_t)stream,
+                       xcd_out_dev, n_workgroups);
+    ADAQP_HIP_TRY(hipGetLastError());
+    return ADAQP_OK;
+}
 
 extern "C" int adaqp_probe_stream(const void *src_dev, void *dst_dev, int64_t bytes, int32_t write_side, void *stream)
 {

@@ -704,6 +704,42 @@ def test_spmm_panels(oracle, dim, ld):
     assert torch.equal(together.view(torch.int32), one_after_the_other.view(torch.int32))
 
 
+def test_non_finite_neighbour_row_and_the_aggregation_paths(oracle):
+    """Inputs must be finite.  What happens otherwise is pinned here so that it cannot change unnoticed: an Inf in
+    one row of H reaches exactly the rows that have an edge to it in the merge-path and tiled kernels (Sec. 2.1
+    Eq. 3 sums over a row's own neighbours); the dense panels multiply every row of H they list by all 32
+    coefficients of a panel column, zeros included, so there it reaches every row of the panels that list the
+    column (0 * Inf = NaN) - and no row outside them."""
+    _say("non-finite row")
+    rng = np.random.default_rng(77)
+    n_rows, n_cols, dim, ld = 200, 640, 64, 64
+    degs = rng.integers(2, 40, size=n_rows)
+    heavy = rng.choice(n_rows, size=40, replace=False)
+    degs[heavy] = rng.integers(150, 400, size=40)
+    rowptr, col, val = _random_graph(rng, n_rows, n_cols, degs)
+    H = rng.standard_normal((n_cols, ld), dtype=np.float32)
+    bad_col = int(col[rowptr[heavy[0]]])                       # a column that a panel row references
+    H[bad_col, 3] = np.inf
+    has_edge = np.array([bad_col in col[rowptr[r]: rowptr[r + 1]] for r in range(n_rows)])
+    assert has_edge.any() and not has_edge.all()
+    merge = _gpu_spmm(rowptr, col, val, 0, n_rows, H, dim)
+    tiled, _, _ = _gpu_spmm_tiled(rowptr, col, val, 0, n_rows, H, dim, ld)
+    for name, got in (("merge path", merge), ("tiled", tiled)):
+        bad_rows = ~np.isfinite(got[:, :dim]).all(axis=1)
+        assert np.array_equal(bad_rows, has_edge), name
+        assert np.isfinite(got[:, [c for c in range(dim) if c != 3]]).all(), name     # only the column of the Inf
+    both, plan = _gpu_spmm_tiled_and_panels(rowptr, col, val, 0, n_rows, H, dim, ld, 150, 64)
+    bad_rows = ~np.isfinite(both[:, :dim]).all(axis=1)
+    assert np.all(bad_rows[has_edge])                          # never fewer rows than the definition
+    panel_rows = plan["panel_rows"].reshape(-1, 32)
+    listing = np.zeros(n_rows, dtype=bool)
+    for rows in panel_rows:
+        rows = rows[rows >= 0]
+        if any(bad_col in col[rowptr[r]: rowptr[r + 1]] for r in rows):
+            listing[rows] = True
+    assert np.array_equal(bad_rows, has_edge | listing)
+
+
 def test_spmm_panels_random_shapes(oracle):
     """Seeded sweep over small shapes: fewer columns than tiles, a single long row, dense blocks, ragged widths."""
     rng = np.random.default_rng(777)
