@@ -195,7 +195,7 @@ def measure_config(name, args, headline, B, torch, np):
     t_gen = time.perf_counter() - t0
     dev = "cuda:0"
     t0 = time.perf_counter()
-    L = LayerStep(p, dev, seed=2306, tiled=False if args.no_tiled else None, panels=not args.no_panels)
+    L = LayerStep(p, dev, seed=2306, tiled=False if args.no_tiled else None, panels=False if args.no_panels else None)
     torch.cuda.synchronize()
     t_plan = time.perf_counter() - t0
     schedule = args.schedule if headline else None
@@ -552,6 +552,41 @@ def measure_config(name, args, headline, B, torch, np):
     return rec
 
 
+def degree_law_check(args, B, torch, np):
+    """c1's sizes with a milder degree law (log-normal instead of Zipf(1.5)): what the library's rules choose there
+    (tiles, panels) and what the other choices would cost.  Not one of the metric's workloads."""
+    from paper_2306_01381_amd.layer import LayerStep
+    from paper_2306_01381_amd.synth import config_by_name, make_partition
+    cfg = config_by_name("c1m")
+    p = make_partition(cfg)
+    deg = np.diff(p.rowptr)
+    out = {"workload": f"{cfg.name}: {cfg.stands_in_for}", "nnz": p.nnz, "max_row": int(deg.max()),
+           "rows_at_or_above_panel_threshold": int(np.count_nonzero(deg >= B.SPMM_PANEL_MIN_ROW)), "ms_per_step": {}}
+    steps = max(3, args.steps // 2)
+    for tag, kw in (("library_rules", {}), ("panels_forced", {"panels": True}), ("tiled_without_panels", {"panels": False}),
+                    ("merge_path", {"tiled": False})):
+        L = LayerStep(p, "cuda:0", seed=2306, **kw)
+        paired = L.tile_off_overlap is not None and L.tile_off_dependent is not None and \
+            bool(L.panels_overlap or L.panels_dependent)
+        desc = L.desc(B.ISOLATED if paired else B.SERIAL)
+        for _ in range(2):
+            B.adaqp_layer_step(desc)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(steps):
+            B.adaqp_layer_step(desc)
+        torch.cuda.synchronize()
+        out["ms_per_step"][tag] = (time.perf_counter() - t) * 1e3 / steps
+        if tag == "library_rules":
+            out["library_rules_chose"] = {"tiled": L.tile_off_overlap is not None,
+                                          "panels": int(L.panels_overlap.c.n_panels + L.panels_dependent.c.n_panels)}
+        del L
+        torch.cuda.empty_cache()
+    best = min(out["ms_per_step"].values())
+    out["library_rules_over_best"] = out["ms_per_step"]["library_rules"] / best
+    return out
+
+
 def short(rec):
     """The record of a non-headline workload, reduced to what the metric asks for."""
     k = rec["kernels"]
@@ -619,6 +654,9 @@ def main():
                 continue
             print(f"bench.py: {name}", file=sys.stderr, flush=True)
             result["configs"][name] = short(measure_config(name, args, False, B, torch, np))
+    if not args.only_headline and args.config == "c1":
+        print("bench.py: c1m (degree-law check)", file=sys.stderr, flush=True)
+        result["degree_law_check"] = degree_law_check(args, B, torch, np)
     if args.calibrate:
         a_ = torch.zeros(1 << 26, dtype=torch.float32, device="cuda:0")
         b_ = torch.empty_like(a_)

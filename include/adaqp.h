@@ -355,6 +355,14 @@ int adaqp_plan_spmm_panels(const int64_t *rowptr_host, const int32_t *col_host, 
                            int32_t *tile_off_inout, int32_t *panel_rows_out, int32_t *pcol_out, float *palpha_out,
                            int32_t *piece_out, int32_t *panel_piece_ptr_out, int32_t *panel_piece_out);
 
+/* Host only: 1 if a panel plan of n_panel_pieces pieces (sizes_out[4] of adaqp_plan_spmm_panels) is worth launching
+ * for rows of dim columns, else 0.  The panel kernel runs one wave per (piece, 128-column chunk); a plan with fewer
+ * than ADAQP_SPMM_PANEL_MIN_WAVES of them (a graph with only a handful of very long rows) leaves most of the GPU
+ * idle and loses against leaving those rows to adaqp_spmm_csr_tiled (measured on a log-normal degree law: one or
+ * two panels cost 0.14 ms where the tiled kernel takes 0.04 ms more for the same rows). */
+#define ADAQP_SPMM_PANEL_MIN_WAVES 2048
+int32_t adaqp_spmm_panels_pay(int64_t n_panel_pieces, int32_t dim);
+
 /* Bytes of workspace adaqp_spmm_csr_panels needs (one [32][dim padded to lines] partial per piece slot). */
 int adaqp_spmm_panels_workspace_bytes(int32_t n_per_tile, int32_t dim, int64_t *bytes_out);
 

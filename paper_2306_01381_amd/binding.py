@@ -99,6 +99,7 @@ _SIGNATURES = {
     "adaqp_plan_spmm_panels": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _vp, _vp,
                                               _vp, _vp, _vp, _vp]),
     "adaqp_spmm_panels_workspace_bytes": (ctypes.c_int, [_i32, _i32, _vp]),
+    "adaqp_spmm_panels_pay": (_i32, [_i64, _i32]),
     "adaqp_spmm_csr_panels": (ctypes.c_int, [ctypes.POINTER(SpmmPanels), _i64, _i64, _vp, _i64, _i64, _i32, _vp,
                                              _i64, _vp, _i64, _vp]),
     "adaqp_assign_bits": (ctypes.c_int, [_i64, _vp, _vp, _i32, _i32, _i32, ctypes.c_double, _vp, _vp, _vp, _vp]),
@@ -338,8 +339,9 @@ def adaqp_spmm_tiled_chunk_cols(col_bounds_host: np.ndarray, dim: int) -> int:
 def adaqp_plan_spmm_panels(rowptr_host: np.ndarray, col_host: np.ndarray, val_host: np.ndarray, row_begin: int,
                            row_end: int, n_cols: int, col_bounds_host: np.ndarray,
                            tile_off: Optional[np.ndarray] = None, min_row_len: int = SPMM_PANEL_MIN_ROW,
-                           piece_cols: int = SPMM_PANEL_PIECE_COLS) -> Optional[dict]:
-    """Host-only.  Returns None when no row of the range has min_row_len entries, else a dict of host arrays
+                           piece_cols: int = SPMM_PANEL_PIECE_COLS, only_if_pays_for_dim: int = 0) -> Optional[dict]:
+    """Host-only.  Returns None when no row of the range has min_row_len entries (or, with only_if_pays_for_dim =
+    the row width, when adaqp_spmm_panels_pay turns the sized plan down), else a dict of host arrays
     (panel_rows, pcol, palpha, piece, panel_piece_ptr, panel_piece) and sizes (n_rows_taken, n_panels, n_groups,
     n_per_tile, n_panel_pieces).  tile_off (the C-contiguous int32 table of adaqp_plan_spmm_tiles for the same
     range) is changed in place: the rows taken are struck from it."""
@@ -359,6 +361,8 @@ def adaqp_plan_spmm_panels(rowptr_host: np.ndarray, col_host: np.ndarray, val_ho
     _check(lib().adaqp_plan_spmm_panels(*args, None, None, None, None, None, None, None), "adaqp_plan_spmm_panels")
     taken, n_panels, n_groups, n_per_tile, n_pieces = (int(x) for x in sizes)
     if taken == 0:
+        return None
+    if only_if_pays_for_dim > 0 and not adaqp_spmm_panels_pay(n_pieces, only_if_pays_for_dim):
         return None
     plan = {
         "n_rows_taken": taken, "n_panels": n_panels, "n_groups": n_groups, "n_per_tile": n_per_tile,
@@ -397,6 +401,11 @@ class DevicePanels:
 
     def __bool__(self) -> bool:
         return self.c.n_panels > 0
+
+
+def adaqp_spmm_panels_pay(n_panel_pieces: int, dim: int) -> bool:
+    """Host-only.  True if a panel plan of that many pieces is worth launching (it fills enough of the GPU)."""
+    return bool(lib().adaqp_spmm_panels_pay(n_panel_pieces, dim))
 
 
 def adaqp_spmm_panels_workspace_bytes(n_per_tile: int, dim: int) -> int:

@@ -324,6 +324,13 @@ extern "C" int adaqp_plan_spmm_panels(const int64_t *rowptr_host, const int32_t 
     return ADAQP_OK;
 }
 
+extern "C" int32_t adaqp_spmm_panels_pay(int64_t n_panel_pieces, int32_t dim)
+{
+    if (n_panel_pieces <= 0 || dim <= 0) return 0;
+    const int64_t chunks = ((int64_t)dim + 127) / 128;
+    return n_panel_pieces * chunks >= ADAQP_SPMM_PANEL_MIN_WAVES ? 1 : 0;
+}
+
 extern "C" int adaqp_spmm_panels_workspace_bytes(int32_t n_per_tile, int32_t dim, int64_t *bytes_out)
 {
     if (!bytes_out || n_per_tile < 0 || dim <= 0) return ADAQP_EINVAL;

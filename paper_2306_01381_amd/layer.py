@@ -89,7 +89,7 @@ def line_padded(a: np.ndarray, device, pad: bool = True) -> torch.Tensor:
 class LayerStep:
     def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False,
                  backward_receive: bool = True, trace: bool = True, fused_receive: bool = False,
-                 tiled: Optional[bool] = None, panels: bool = True, panel_min_row=B.SPMM_PANEL_MIN_ROW,
+                 tiled: Optional[bool] = None, panels: Optional[bool] = None, panel_min_row=B.SPMM_PANEL_MIN_ROW,
                  panel_piece_cols: int = B.SPMM_PANEL_PIECE_COLS):
         self.p = p
         self.device = torch.device(device)
@@ -132,7 +132,8 @@ class LayerStep:
         # tiled=None lets the library decide per row range (adaqp_spmm_tiled_pays: mean row length).
         self.tile_off_overlap = self.tile_off_dependent = None
         self.tile_chunk_overlap = self.tile_chunk_dependent = 0
-        # within a tiled range, rows with thousands of entries go into dense panels for the matrix cores
+        # within a tiled range, rows with thousands of entries go into dense panels for the matrix cores.
+        # panels=None: where the library says the plan fills enough of the GPU (adaqp_spmm_panels_pay); True: always
         self.panels_overlap = self.panels_dependent = B.DevicePanels(None)
         # panel_min_row: one threshold, or one per row range (overlap, dependent)
         min_row_o, min_row_d = panel_min_row if isinstance(panel_min_row, tuple) else (panel_min_row, panel_min_row)
@@ -141,9 +142,10 @@ class LayerStep:
         if pad and tiled is not False:
             if oe > ob and (tiled or B.adaqp_spmm_tiled_pays(oe - ob, self.overlap_nnz)):
                 bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, ob, oe, p.feat.shape[0])
-                if panels:
+                if panels is not False:
                     self.panels_overlap = B.DevicePanels(B.adaqp_plan_spmm_panels(
-                        p.rowptr, p.col, p.val, ob, oe, p.feat.shape[0], bounds, off, min_row_o, panel_piece_cols), dev)
+                        p.rowptr, p.col, p.val, ob, oe, p.feat.shape[0], bounds, off, min_row_o, panel_piece_cols,
+                        only_if_pays_for_dim=0 if panels else cfg.dim), dev)
                 self.tile_off_overlap = torch.from_numpy(off).to(dev)
                 self.tile_chunk_overlap = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)
                 # partial sums of the tiled kernel, then the piece sums of the panel kernel (they may run together)
@@ -151,9 +153,10 @@ class LayerStep:
                            + B.adaqp_spmm_panels_workspace_bytes(self.panels_overlap.n_per_tile, cfg.dim))
             if de > db and (tiled or B.adaqp_spmm_tiled_pays(de - db, self.dependent_nnz)):
                 bounds, off = B.adaqp_plan_spmm_tiles(p.rowptr, p.col, db, de, p.feat.shape[0])
-                if panels:
+                if panels is not False:
                     self.panels_dependent = B.DevicePanels(B.adaqp_plan_spmm_panels(
-                        p.rowptr, p.col, p.val, db, de, p.feat.shape[0], bounds, off, min_row_d, panel_piece_cols), dev)
+                        p.rowptr, p.col, p.val, db, de, p.feat.shape[0], bounds, off, min_row_d, panel_piece_cols,
+                        only_if_pays_for_dim=0 if panels else cfg.dim), dev)
                 self.tile_off_dependent = torch.from_numpy(off).to(dev)
                 self.tile_chunk_dependent = B.adaqp_spmm_tiled_chunk_cols(bounds, cfg.dim)
                 ws_d = max(ws_d, B.adaqp_spmm_tiled_workspace_bytes(de - db, cfg.dim)

@@ -36,6 +36,7 @@ class PartitionConfig:
     draw_inflation: float = 1.0  # extra draws to make up for duplicates removed per row
     stands_in_for: str = ""
     aggregator: str = "gcn"     # coefficients: "gcn" symmetric normalisation | "mean" (GraphSAGE-style, 1 / row degree)
+    degree_law: str = "zipf"    # row degrees: "zipf" (Zipf(1.5), clipped) | "lognormal" (sigma 1: a milder skew)
 
 
 # Zipf(1.5) samples are clipped at this raw value; with the clipped mean (about 170) the largest degree
@@ -50,6 +51,11 @@ CONFIGS: Dict[str, PartitionConfig] = {
     "c1": PartitionConfig("c1", 58_000, 40_000, 790, 602, 30_000, 3, "normal", "mix_c1", seed=1,
                           draw_inflation=1.17,
                           stands_in_for="one of 4 partitions of a 233K-node / 114M-edge graph, 602 features"),
+    # c1 with a milder degree law (same sizes, same mean degree): not one of the metric's workloads; it checks that the
+    # rules that pick the aggregation kernels (tiles, panels) do not hinge on c1's heavy tail
+    "c1m": PartitionConfig("c1m", 58_000, 40_000, 425, 602, 30_000, 3, "normal", "mix_c1", seed=1,
+                           draw_inflation=1.17, degree_law="lognormal",
+                           stands_in_for="c1's sizes with log-normal row degrees (sigma 1) instead of Zipf(1.5)"),
     "c2": PartitionConfig("c2", 306_000, 150_000, 23.4, 256, 120_000, 7, "relu", "all2", seed=2,
                           draw_inflation=1.005,
                           stands_in_for="one of 8 partitions of a 2.45M-node / 62M-edge graph, hidden 256"),
@@ -94,8 +100,13 @@ class Partition:
         return int(self.col.shape[0])
 
 
-def _degrees(rng: np.random.Generator, n: int, mean: float, cap: int) -> np.ndarray:
-    raw = np.minimum(rng.zipf(1.5, size=n), _ZIPF_CLIP).astype(np.float64)
+def _degrees(rng: np.random.Generator, n: int, mean: float, cap: int, law: str = "zipf") -> np.ndarray:
+    if law == "zipf":
+        raw = np.minimum(rng.zipf(1.5, size=n), _ZIPF_CLIP).astype(np.float64)
+    elif law == "lognormal":
+        raw = rng.lognormal(0.0, 1.0, size=n)
+    else:
+        raise ValueError(law)
     deg = np.rint(raw * (mean / raw.mean())).astype(np.int64)
     return np.clip(deg, 1, cap)
 
@@ -120,7 +131,7 @@ def _forward_graph(rng: np.random.Generator, cfg: PartitionConfig):
     n_marg = min(n_local, cfg.n_send)
     n_central = n_local - n_marg
 
-    deg = _degrees(rng, n_local, cfg.mean_degree, cap=max(1, n_local // 2))
+    deg = _degrees(rng, n_local, cfg.mean_degree, cap=max(1, n_local // 2), law=cfg.degree_law)
     draws = np.maximum(1, np.rint(deg * cfg.draw_inflation)).astype(np.int64)
     row_of_draw = np.repeat(np.arange(n_local, dtype=np.int64), draws)
     n_draw = int(row_of_draw.shape[0])

@@ -42,7 +42,7 @@ def digest(p) -> dict:
 
 def main() -> None:
     result = {"numpy": np.__version__}
-    for name in ("c0", "c1", "c2", "c3", "c4"):
+    for name in ("c0", "c1", "c2", "c3", "c4", "c1m"):
         result[name] = digest(make_partition(CONFIGS[name]))
         print(name, result[name]["nnz"], flush=True)
     with open(os.path.join(HERE, "synth_digest.json"), "w") as f:

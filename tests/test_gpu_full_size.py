@@ -57,7 +57,7 @@ def _check_all_rows(oracle, p, H_host, out, lo, hi, dim, what):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c1m"])
 def test_full_size_layer_step(oracle, name):
     """One layer step at the benchmark's size and launch configuration; EVERY packed byte, (Z, S) pair,
     de-quantised halo element and aggregated output element is compared with the oracle."""

@@ -1003,7 +1003,7 @@ def test_layer_step_with_panels(oracle, name):
     packed_w, params_w, feat_w, out64, mag = _oracle_layer(oracle, p, seed)
     first = None
     for schedule in (B.SERIAL, B.ISOLATED, B.FREE):
-        L = LayerStep(p, DEV, seed=seed, tiled=True, backward_receive=False, panel_min_row=min_row)
+        L = LayerStep(p, DEV, seed=seed, tiled=True, panels=True, backward_receive=False, panel_min_row=min_row)
         assert L.panels_overlap and L.panels_dependent
         n_taken = int(np.count_nonzero(L.panels_overlap.tensors["panel_rows"].cpu().numpy() >= 0)) + \
             int(np.count_nonzero(L.panels_dependent.tensors["panel_rows"].cpu().numpy() >= 0))
@@ -1043,7 +1043,8 @@ def test_layer_step_captured_in_a_graph(schedule_name):
     cfg = p.cfg
     if schedule_name.endswith("tiled_panels"):
         deg = np.diff(p.rowptr)
-        L = LayerStep(p, DEV, seed=99, tiled=True, panel_min_row=max(int(np.quantile(deg[deg > 0], 0.9)), 2))
+        L = LayerStep(p, DEV, seed=99, tiled=True, panels=True,
+                      panel_min_row=max(int(np.quantile(deg[deg > 0], 0.9)), 2))
         assert L.panels_overlap and L.panels_dependent
     else:
         L = LayerStep(p, DEV, seed=99)

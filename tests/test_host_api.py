@@ -324,6 +324,31 @@ def test_plan_spmm_panels_random_graphs():
             assert np.array_equal(dense[k], want), (case, k, r)
 
 
+def test_rule_that_decides_whether_a_panel_plan_pays():
+    # one wave per (piece, 128-column chunk); fewer than ADAQP_SPMM_PANEL_MIN_WAVES of them do not fill the GPU
+    assert not B.adaqp_spmm_panels_pay(0, 602) and not B.adaqp_spmm_panels_pay(100, 0)
+    assert not B.adaqp_spmm_panels_pay(60, 602)            # one panel of a 602-column graph: 300 waves
+    assert B.adaqp_spmm_panels_pay(1150, 602)              # eighteen panels: 5750 waves
+    assert B.adaqp_spmm_panels_pay(2048, 128) and not B.adaqp_spmm_panels_pay(2047, 128)
+    assert B.adaqp_spmm_panels_pay(410, 602) and not B.adaqp_spmm_panels_pay(409, 602)      # 5 chunks per piece
+    # the planner binding turns a sized plan down on request and then leaves the tile table alone
+    rng = np.random.default_rng(4)
+    n_rows, n_cols = 40, 300
+    degs = np.full(n_rows, 5)
+    degs[:3] = 200
+    rowptr = np.zeros(n_rows + 1, dtype=np.int64)
+    np.cumsum(degs, out=rowptr[1:])
+    col = np.concatenate([np.sort(rng.choice(n_cols, size=d, replace=False)) for d in degs]).astype(np.int32)
+    val = rng.standard_normal(col.shape[0]).astype(np.float32)
+    bounds, off = B.adaqp_plan_spmm_tiles(rowptr, col, 0, n_rows, n_cols)
+    before = off.copy()
+    assert B.adaqp_plan_spmm_panels(rowptr, col, val, 0, n_rows, n_cols, bounds, off, 100, 64,
+                                    only_if_pays_for_dim=128) is None
+    assert np.array_equal(off, before)
+    assert B.adaqp_plan_spmm_panels(rowptr, col, val, 0, n_rows, n_cols, bounds, off, 100, 64) is not None
+    assert not np.array_equal(off, before)
+
+
 def test_layer_desc_mirror_matches_the_library():
     import ctypes
     assert int(B.lib().adaqp_layer_desc_bytes()) == ctypes.sizeof(B.LayerDesc)
