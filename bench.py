@@ -346,11 +346,33 @@ def measure_config(name, args, headline, B, torch, np):
             B.adaqp_unpack_dequant_add(packs[0], pars[0], pl.bits, pl.row_offset, pl.halo_idx, pl.seg_order,
                                        pl.seg_ptr, dim, srcs[0], stream=st)
 
+        def a_floor(i):
+            k = i % n_copies
+            B.adaqp_probe_unpack_dequant_add(packs[k], pars[k], pl.bits, pl.row_offset, pl.halo_idx, pl.seg_order,
+                                             pl.seg_ptr, dim, srcs[k], stream=st)
+
+        upd_bytes = (n_seg * dim * 4) // 16 * 16
+
+        def stream_update(i):
+            k = i % n_copies
+            B.adaqp_probe_stream(small[k], flat[k], upd_bytes, 2, stream=st)
+
         t = event_time_ms(st, a_cold, creps)
         tw = event_time_ms(st, a_warm, creps)
         t_med, t_min = per_launch_ms(st, a_cold, creps)
-        kernels["unpack_dequant_add"] = codec_entry(t, tw, t_med, t_min, abytes,
-                                                    {"rows": n_seg, "messages": pl.n, "launches": creps})
+        extra = {"rows": n_seg, "messages": pl.n, "launches": creps}
+        if dim % 32 == 0 and dim <= 512:
+            t_floor = event_time_ms(st, a_floor, creps)     # leaves meaningless bits in the rows: timed last
+            extra["floor_no_compute_twin"] = {
+                "ms": t_floor, "frac_hbm": abytes / t_floor / 1e6 / HBM_PEAK_GBPS, "kernel_over_floor": t / t_floor,
+                "note": "adaqp_probe_unpack_dequant_add: same grid, index loads, row and packed-word loads and row "
+                        "stores, no decoding / adding"}
+        t_su = event_time_ms(st, stream_update, creps)
+        extra["stream_of_same_size"] = {
+            "ms": t_su, "frac_hbm": upd_bytes * 2.125 / t_su / 1e6 / HBM_PEAK_GBPS,
+            "note": "adaqp_probe_stream: as many row bytes read front to back and written back in place "
+                    "(non-temporal loads and stores, 4 KiB per wave), an eighth of them read beside"}
+        kernels["unpack_dequant_add"] = codec_entry(t, tw, t_med, t_min, abytes, extra)
     del srcs, packs, pars, small, flat
     # the stream probes wrote into the step's own operand (copy 0): put the inputs back before the aggregation is timed
     if cfg.backward:

@@ -29,13 +29,29 @@ int adaqp_probe_quantize_pack(const float *feat_dev, int64_t n_feat_rows, int64_
                               int64_t n_send, uint8_t *packed_dev, int64_t packed_bytes, float *params_dev,
                               void *stream);
 
+/* The no-compute twin of adaqp_unpack_dequant_add (backward receive: Eq. 5 applied to every message, messages added
+ * to their gradient rows in slot order): the same launch shape, the same loads of segment bounds, slot numbers,
+ * index entries, parameters, gradient rows and packed words, the same stores of the rows - but a message's words
+ * are xor-ed into its row instead of being decoded and added.  The rows named by dst_idx_dev end up holding
+ * meaningless bits; other rows are not touched.  Only for the shape the full-size workloads take (base 128-byte
+ * aligned, ld a multiple of 32, dim a multiple of 32 and at most 512); otherwise EINVAL.
+ * Errors: as adaqp_unpack_dequant_add. */
+int adaqp_probe_unpack_dequant_add(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
+                                   const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                                   const int32_t *dst_idx_dev, int64_t n_recv, const int32_t *seg_order_dev,
+                                   const int64_t *seg_ptr_dev, int64_t n_seg, int32_t dim, float *grad_dev,
+                                   int64_t n_grad_rows, int64_t ld, void *stream);
+
 /* A plain stream over `bytes` bytes (a multiple of 16, both pointers 16-byte aligned):
  *   write_side = 0: reads src_dev[0, bytes) front to back with 16-byte non-temporal loads, 2 KiB per wave, and
  *                   writes bytes / 8 to dst_dev (the traffic mix of the send side: 4-bit codes for fp32 values);
  *   write_side = 1: writes dst_dev[0, bytes) front to back with 16-byte non-temporal stores, 4 KiB per wave, and
- *                   reads bytes / 8 from src_dev (the mix of the receive side).
+ *                   reads bytes / 8 from src_dev (the mix of the receive side);
+ *   write_side = 2: reads dst_dev[0, bytes) front to back (non-temporal loads), reads bytes / 8 from src_dev and
+ *                   writes dst_dev[0, bytes) back in place (non-temporal stores), 4 KiB per wave: the mix of the
+ *                   backward receive, which adds messages to gradient rows.
  * The small side needs bytes / 8 + 4096 bytes.  What is written is derived from what is read.
- * Errors: EINVAL (null, alignment, negative size), ESIZE (more than 2^40 bytes), EHIP. */
+ * Errors: EINVAL (null, alignment, negative size, another write_side), ESIZE (more than 2^40 bytes), EHIP. */
 int adaqp_probe_stream(const void *src_dev, void *dst_dev, int64_t bytes, int32_t write_side, void *stream);
 
 /* Launches a 1-D grid of n_workgroups workgroups (256 threads, as every kernel of the library) and records the XCD

@@ -108,6 +108,8 @@ _SIGNATURES = {
                                              _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "adaqp_layer_step": (ctypes.c_int, [ctypes.POINTER(LayerDesc)]),
     "adaqp_probe_quantize_pack": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _vp, _i64, _vp, _vp]),
+    "adaqp_probe_unpack_dequant_add": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _i32,
+                                                _vp, _i64, _i64, _vp]),
     "adaqp_probe_stream": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp]),
     "adaqp_probe_xcd_of_workgroup": (ctypes.c_int, [_vp, _i32, _vp]),
     "adaqp_layer_desc_bytes": (_i64, []),
@@ -501,15 +503,34 @@ def adaqp_probe_quantize_pack(feat: torch.Tensor, dim: int, send_idx: torch.Tens
            "adaqp_probe_quantize_pack")
 
 
-def adaqp_probe_stream(src: torch.Tensor, dst: torch.Tensor, nbytes: int, write_side: bool,
+def adaqp_probe_unpack_dequant_add(packed: torch.Tensor, params: torch.Tensor, bits: torch.Tensor,
+                                   row_offset: torch.Tensor, dst_idx: torch.Tensor, seg_order: torch.Tensor,
+                                   seg_ptr: torch.Tensor, dim: int, grad: torch.Tensor,
+                                   stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Measurement aid (include/adaqp_probe.h): the no-compute twin of adaqp_unpack_dequant_add."""
+    gp, n_rows, ld = _matrix(grad, "grad")
+    _check(lib().adaqp_probe_unpack_dequant_add(_dev(packed, torch.uint8, "packed"), packed.numel(),
+                                                _dev(params, torch.float32, "params"),
+                                                _dev(bits, torch.uint8, "bits"),
+                                                _dev(row_offset, torch.int64, "row_offset"),
+                                                _dev(dst_idx, torch.int32, "dst_idx"), dst_idx.shape[0],
+                                                _dev(seg_order, torch.int32, "seg_order"),
+                                                _dev(seg_ptr, torch.int64, "seg_ptr"), seg_ptr.shape[0] - 1,
+                                                dim, gp, n_rows, ld, _stream(stream)),
+           "adaqp_probe_unpack_dequant_add")
+
+
+def adaqp_probe_stream(src: torch.Tensor, dst: torch.Tensor, nbytes: int, write_side: int,
                        stream: Optional[torch.cuda.Stream] = None) -> None:
-    """Measurement aid (include/adaqp_probe.h): a plain stream over nbytes bytes of src (read side) or dst."""
+    """Measurement aid (include/adaqp_probe.h): a plain stream over nbytes bytes of src (write_side 0), of dst
+    (1), or of dst read and written back in place (2)."""
+    write_side = int(write_side)
     big, small = (dst, src) if write_side else (src, dst)
     if big.numel() * big.element_size() < nbytes or small.numel() * small.element_size() < nbytes // 8 + 4096:
         raise ValueError("adaqp_probe_stream: a buffer is smaller than the stream")
     if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
         raise TypeError("adaqp_probe_stream needs contiguous device tensors")
-    _check(lib().adaqp_probe_stream(src.data_ptr(), dst.data_ptr(), nbytes, 1 if write_side else 0, _stream(stream)),
+    _check(lib().adaqp_probe_stream(src.data_ptr(), dst.data_ptr(), nbytes, write_side, _stream(stream)),
            "adaqp_probe_stream")
 
 

@@ -757,7 +757,9 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_add_kernel(const Dequan
 // hear from one or two peers, so a wave per row spends its life waiting on a chain of dependent loads (segment
 // bounds -> slot numbers -> index entries -> row and packed words); here the chain is walked once for S rows,
 // and their row loads and packed words are all in flight together.  Same arithmetic and order per row as above.
-template <int VW, int NV, int S, bool STREAM>
+// PROBE: the no-compute twin - the same loads and stores at the same addresses, but a message's words are xor-ed
+// into its row instead of being decoded and added (the rows end up holding meaningless bits).
+template <int VW, int NV, int S, bool STREAM, bool PROBE>
 __global__ __launch_bounds__(kBlock) void unpack_dequant_add4_kernel(const DequantAddArgs a)
 {
     constexpr int G = 4;
@@ -852,6 +854,15 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_add4_kernel(const Dequa
             const int32_t b = __builtin_amdgcn_readlane(my_b, j0 + u);
             if (b == 0) continue;
             const int32_t seg = __builtin_amdgcn_readlane(my_seg, j0 + u);
+            if (PROBE) {
+#pragma unroll
+                for (int i = 0; i < S; ++i)
+                    if (seg == i)
+#pragma unroll
+                        for (int v = 0; v < NV; ++v)
+                            acc[i][v][0] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, acc[i][v][0]) ^ w[u][v]);
+                continue;
+            }
             const float Z = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_z), j0 + u));
             const float Sc = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, my_s), j0 + u));
             const uint32_t mask = (1u << b) - 1u;
@@ -1136,11 +1147,10 @@ extern "C" int adaqp_unpack_dequant(const uint8_t *packed_dev, int64_t packed_by
     return ADAQP_OK;
 }
 
-extern "C" int adaqp_unpack_dequant_add(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
-                                        const uint8_t *bits_dev, const int64_t *row_offset_dev,
-                                        const int32_t *dst_idx_dev, int64_t n_recv, const int32_t *seg_order_dev,
-                                        const int64_t *seg_ptr_dev, int64_t n_seg, int32_t dim, float *grad_dev,
-                                        int64_t n_grad_rows, int64_t ld, void *stream)
+static int dequant_add_launch(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
+                              const uint8_t *bits_dev, const int64_t *row_offset_dev, const int32_t *dst_idx_dev,
+                              int64_t n_recv, const int32_t *seg_order_dev, const int64_t *seg_ptr_dev, int64_t n_seg,
+                              int32_t dim, float *grad_dev, int64_t n_grad_rows, int64_t ld, void *stream, bool probe)
 {
     if (n_recv < 0 || n_seg < 0 || dim <= 0 || ld < dim || n_grad_rows < 0 || packed_bytes < 0) return ADAQP_EINVAL;
     if (n_recv == 0 || n_seg == 0) return ADAQP_OK;
@@ -1180,13 +1190,21 @@ extern "C" int adaqp_unpack_dequant_add(const uint8_t *packed_dev, int64_t packe
     const dim3 grid4((unsigned)((n_seg + seg_per_wave * kWavesPerBlock - 1) / (seg_per_wave * kWavesPerBlock)));
 #define ADAQP_ADD(VW_, ST_)                                                                                        \
     do {                                                                                                           \
-        if (nv == 1) hipLaunchKernelGGL((unpack_dequant_add4_kernel<VW_, 1, 4, ST_>), grid4, dim3(kBlock), 0, st, a);   \
-        else if (nv == 2) hipLaunchKernelGGL((unpack_dequant_add4_kernel<VW_, 2, 4, ST_>), grid4, dim3(kBlock), 0, st, a); \
+        if (nv == 1) hipLaunchKernelGGL((unpack_dequant_add4_kernel<VW_, 1, 4, ST_, false>), grid4, dim3(kBlock), 0, st, a);   \
+        else if (nv == 2) hipLaunchKernelGGL((unpack_dequant_add4_kernel<VW_, 2, 4, ST_, false>), grid4, dim3(kBlock), 0, st, a); \
         else if (nv == 3) hipLaunchKernelGGL((unpack_dequant_add_kernel<VW_, 3, ST_>), grid, dim3(kBlock), 0, st, a);   \
         else hipLaunchKernelGGL((unpack_dequant_add_kernel<VW_, 4, ST_>), grid, dim3(kBlock), 0, st, a);                \
     } while (0)
     // rows that are whole 128-byte lines (line-padded layout, dim a multiple of 32) are written back non-temporally
     const bool whole_lines = line_padded(grad_dev, ld) && dim % 32 == 0;
+    if (probe) {
+        // the twin exists for the shape the full-size workloads take: whole-line rows of at most 512 columns
+        if (vw != 4 || !whole_lines || nv > 2) return ADAQP_EINVAL;
+        if (nv == 1) hipLaunchKernelGGL((unpack_dequant_add4_kernel<4, 1, 4, true, true>), grid4, dim3(kBlock), 0, st, a);
+        else hipLaunchKernelGGL((unpack_dequant_add4_kernel<4, 2, 4, true, true>), grid4, dim3(kBlock), 0, st, a);
+        ADAQP_HIP_TRY(hipGetLastError());
+        return ADAQP_OK;
+    }
     if (vw == 4 && whole_lines) ADAQP_ADD(4, true);
     else if (vw == 4) ADAQP_ADD(4, false);
     else if (vw == 2) ADAQP_ADD(2, false);
@@ -1194,4 +1212,25 @@ extern "C" int adaqp_unpack_dequant_add(const uint8_t *packed_dev, int64_t packe
 #undef ADAQP_ADD
     ADAQP_HIP_TRY(hipGetLastError());
     return ADAQP_OK;
+}
+
+extern "C" int adaqp_unpack_dequant_add(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
+                                        const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                                        const int32_t *dst_idx_dev, int64_t n_recv, const int32_t *seg_order_dev,
+                                        const int64_t *seg_ptr_dev, int64_t n_seg, int32_t dim, float *grad_dev,
+                                        int64_t n_grad_rows, int64_t ld, void *stream)
+{
+    return dequant_add_launch(packed_dev, packed_bytes, params_dev, bits_dev, row_offset_dev, dst_idx_dev, n_recv,
+                              seg_order_dev, seg_ptr_dev, n_seg, dim, grad_dev, n_grad_rows, ld, stream, false);
+}
+
+extern "C" int adaqp_probe_unpack_dequant_add(const uint8_t *packed_dev, int64_t packed_bytes, const float *params_dev,
+                                              const uint8_t *bits_dev, const int64_t *row_offset_dev,
+                                              const int32_t *dst_idx_dev, int64_t n_recv,
+                                              const int32_t *seg_order_dev, const int64_t *seg_ptr_dev, int64_t n_seg,
+                                              int32_t dim, float *grad_dev, int64_t n_grad_rows, int64_t ld,
+                                              void *stream)
+{
+    return dequant_add_launch(packed_dev, packed_bytes, params_dev, bits_dev, row_offset_dev, dst_idx_dev, n_recv,
+                              seg_order_dev, seg_ptr_dev, n_seg, dim, grad_dev, n_grad_rows, ld, stream, true);
 }

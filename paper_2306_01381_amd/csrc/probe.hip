@@ -48,6 +48,31 @@ __global__ __launch_bounds__(kBlock) void stream_write_kernel(const uint32_t *sr
     }
 }
 
+// Wave w reads K consecutive KiB of dst and K * 128 bytes of src, and writes the K KiB back.
+template <int K>
+__global__ __launch_bounds__(kBlock) void stream_update_kernel(const uint32_t *src, int64_t n_vec, float *dst)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t base = w * (kWave * K);
+    uint32_t q[K / 2];
+    float4_t x[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+        int64_t i = base + j * kWave + lane;
+        i = i < n_vec ? i : n_vec - 1;
+        x[j] = __builtin_nontemporal_load(reinterpret_cast<const float4_t *>(dst) + i);
+    }
+#pragma unroll
+    for (int j = 0; j < K / 2; ++j) q[j] = src[w * (kWave * (K / 2)) + j * kWave + lane];
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+        const int64_t i = base + j * kWave + lane;
+        x[j][0] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, x[j][0]) ^ (q[j / 2] >> (16 * (j & 1))));
+        if (i < n_vec) __builtin_nontemporal_store(x[j], reinterpret_cast<float4_t *>(dst) + i);
+    }
+}
+
 // Which XCD each workgroup of a 1-D grid runs on (hardware register XCC_ID).
 __global__ __launch_bounds__(kBlock) void xcd_of_workgroup_kernel(int32_t *out, int32_t n)
 {
@@ -80,7 +105,14 @@ extern "C" int adaqp_probe_stream(const void *src_dev, void *dst_dev, int64_t by
     if (bytes > ((int64_t)1 << 40)) return ADAQP_ESIZE;
     const int64_t n_vec = bytes / 16;
     hipStream_t st = (hipStream_t)stream;
-    if (write_side) {
+    if (write_side < 0 || write_side > 2) return ADAQP_EINVAL;
+    if (write_side == 2) {
+        constexpr int K = 4;
+        const int64_t waves = (n_vec + kWave * K - 1) / (kWave * K);
+        const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+        hipLaunchKernelGGL(stream_update_kernel<K>, dim3((unsigned)blocks), dim3(kBlock), 0, st,
+                           static_cast<const uint32_t *>(src_dev), n_vec, static_cast<float *>(dst_dev));
+    } else if (write_side) {
         constexpr int K = 4;
         const int64_t waves = (n_vec + kWave * K - 1) / (kWave * K);
         const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;

@@ -77,3 +77,45 @@ def test_stream_probe_stays_inside_its_buffers():
     assert bool((big[nbytes:] == 0x5A).all())
     with pytest.raises(B.AdaqpError):
         B.adaqp_probe_stream(big, small, 24, False)                 # not a multiple of 16
+    nb = 1_000_000 // 16 * 16
+    buf = torch.full((nb + 4096,), 3, dtype=torch.uint8, device=DEV)
+    side = torch.zeros(nb // 8 + 4096, dtype=torch.uint8, device=DEV)
+    buf[nb:] = 0x5A
+    B.adaqp_probe_stream(side, buf[:nb], nb, 2)                     # in place; xor with zeros changes nothing
+    torch.cuda.synchronize()
+    assert bool((buf[nb:] == 0x5A).all()) and bool((buf[:nb] == 3).all())
+    with pytest.raises(B.AdaqpError):
+        B.adaqp_probe_stream(side, buf[:nb], nb, 3)
+
+
+@pytest.mark.parametrize("dim", [128, 256, 512])
+def test_backward_receive_twin_touches_only_the_destination_rows(dim):
+    _say(f"probe backward receive twin dim={dim}")
+    rng = np.random.default_rng(dim)
+    n_rows, n = 300, 700
+    bits = rng.choice(np.array([2, 4, 8], dtype=np.uint8), size=n)
+    peer = np.sort(rng.integers(0, 5, size=n)).astype(np.int32)
+    perm, off, pbp = B.adaqp_plan_layout(dim, bits, peer, 5)
+    s_bits = np.ascontiguousarray(bits[perm])
+    packed = rng.integers(1, 256, size=int(pbp[-1]), dtype=np.uint8)
+    params = rng.standard_normal((n, 2), dtype=np.float32)
+    dst = rng.integers(100, 250, size=n).astype(np.int32)
+    order, seg_ptr = B.adaqp_plan_recv_segments(dst)
+    grad0 = rng.standard_normal((n_rows, dim), dtype=np.float32)
+    got = torch.from_numpy(grad0).to(DEV)
+    B.adaqp_probe_unpack_dequant_add(torch.from_numpy(packed).to(DEV), torch.from_numpy(params).to(DEV),
+                                     torch.from_numpy(s_bits).to(DEV), torch.from_numpy(off).to(DEV),
+                                     torch.from_numpy(dst).to(DEV), torch.from_numpy(order).to(DEV),
+                                     torch.from_numpy(seg_ptr).to(DEV), dim, got)
+    torch.cuda.synchronize()
+    g = got.cpu().numpy().view(np.uint32)
+    touched = np.zeros(n_rows, dtype=bool)
+    touched[dst] = True
+    assert np.array_equal(g[~touched], grad0.view(np.uint32)[~touched]), "a row no message names was written"
+    assert not np.array_equal(g[touched], grad0.view(np.uint32)[touched])
+    with pytest.raises(B.AdaqpError):                               # 600 columns: not the twin's shape
+        wide = torch.zeros((n_rows, 608), dtype=torch.float32, device=DEV)
+        B.adaqp_probe_unpack_dequant_add(torch.from_numpy(packed).to(DEV), torch.from_numpy(params).to(DEV),
+                                         torch.from_numpy(s_bits).to(DEV), torch.from_numpy(off).to(DEV),
+                                         torch.from_numpy(dst).to(DEV), torch.from_numpy(order).to(DEV),
+                                         torch.from_numpy(seg_ptr).to(DEV), 600, wide[:, :600])
