@@ -260,10 +260,13 @@ extern "C" int adaqp_plan_spmm_panels(const int64_t *rowptr_host, const int32_t 
                         if (k < len) where[(size_t)c] = G;
                     }
                 }
-                for (int64_t s0 = 0; s0 < ng; s0 += piece_groups)
-                    lists[t].push_back(Piece{(int32_t)p, (int32_t)(n_groups + s0),
-                                             (int32_t)(n_groups + std::min<int64_t>(s0 + piece_groups, ng)),
+                // as few pieces as piece_cols allows, equal to within one group (pieces of one size finish together)
+                const int64_t n_cut = (ng + piece_groups - 1) / piece_groups;
+                for (int64_t q = 0; q < n_cut; ++q) {
+                    const int64_t s0 = ng * q / n_cut, s1 = ng * (q + 1) / n_cut;
+                    lists[t].push_back(Piece{(int32_t)p, (int32_t)(n_groups + s0), (int32_t)(n_groups + s1),
                                              distinct[at + (size_t)(s0 * 8)]});
+                }
                 n_groups += ng;
             }
             at = end;
