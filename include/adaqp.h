@@ -342,7 +342,8 @@ typedef struct adaqp_spmm_panels {
  * range (the pieces of a panel follow the same eight column ranges, so that each L2 keeps seeing one range).
  * Rows are taken in order of descending length (ties: ascending row), 32 per panel; the last panel may be
  * partly filled.  Every (panel, tile) column list is padded to a multiple of 8 with coefficient 0 and cut
- * into pieces of piece_cols columns; a tile's pieces are listed in order of their first column.
+ * into as few pieces of at most piece_cols columns as that takes, equal in size to within one group of 8; a tile's
+ * pieces are listed in order of their first column.
  * Call twice: first with panel_rows_out NULL, which only fills sizes_out[5] = { rows taken, n_panels,
  * n_groups, n_per_tile, n_panel_pieces }; then with arrays of those sizes (layouts as in adaqp_spmm_panels).
  * tile_off_inout (may be NULL): adaqp_plan_spmm_tiles' table for the range; on the filling call all entries of
