@@ -34,6 +34,8 @@ namespace {
 constexpr int kTiles = ADAQP_SPMM_TILES;
 constexpr int kPanelRows = ADAQP_SPMM_PANEL_ROWS;
 constexpr int kChunk = 128;                 // feature columns per wave
+constexpr int kLdsPerCu = 160 * 1024;       // gfx950
+constexpr int kPanelIdleLds = kLdsPerCu / 3 + 1024;     // two workgroups fit a CU, three do not
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
@@ -389,7 +391,12 @@ extern "C" int adaqp_spmm_csr_panels(const adaqp_spmm_panels *p, int64_t row_beg
     const int64_t blocks = blocks_per_tile * kTiles * n_chunks;
     if (blocks > 0x7FFFFFFF) return ADAQP_ESIZE;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(spmm_panel_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+    // Two workgroups per CU, i.e. two waves per SIMD: kPanelIdleLds bytes of dynamic LDS that the kernel never
+    // touches keep a third workgroup off the CU.  Measured on MI355X: a SIMD's fp32 MFMA rate is 98 % of peak with
+    // one to three waves issuing MFMAs back to back and 80 % with four, the kernel alone is 5 % faster at two waves
+    // than at the four its registers allow, and next to the tiled kernel (adaqp_layer_step's two-stream schedules)
+    // the registers it leaves free let more of that kernel's waves onto the SIMD.
+    hipLaunchKernelGGL(spmm_panel_kernel, dim3((unsigned)blocks), dim3(kBlock), (size_t)kPanelIdleLds, st, a);
     ADAQP_HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(spmm_panel_reduce_kernel, dim3((unsigned)(p->n_panels * kPanelRows)), dim3(kBlock), 0, st, a);
     ADAQP_HIP_TRY(hipGetLastError());
