@@ -269,6 +269,15 @@ def test_plan_spmm_panels():
                 c = plan["pcol"][g0:g1].reshape(-1)
                 assert c.min() >= bounds[t] and (t == B.SPMM_TILES - 1 or c.max() < bounds[t + 1])
         assert used == plan["n_panel_pieces"]
+        # the pieces of one (panel, tile): as few as piece_cols allows, equal in size to within one group
+        sizes = {}
+        for p_ in range(plan["n_panels"]):
+            for pid in plan["panel_piece"][plan["panel_piece_ptr"][p_]: plan["panel_piece_ptr"][p_ + 1]]:
+                g0, g1 = plan["piece"][pid // npt, pid % npt]
+                sizes.setdefault((p_, int(pid) // npt), []).append(int(g1 - g0))
+        for key, sz in sizes.items():
+            assert max(sz) - min(sz) <= 1, (key, sz)
+            assert len(sz) == -(-sum(sz) // (piece_cols // 8)), (key, sz)
         # the rows taken are struck from the tile table, the others are untouched
         taken = np.zeros(re - rb, dtype=bool)
         taken[np.array(want_rows, dtype=np.int64) - rb] = True
