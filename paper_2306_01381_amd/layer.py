@@ -90,7 +90,7 @@ class LayerStep:
     def __init__(self, p: Partition, device="cuda:0", seed: int = 0, pad: bool = True, use_recv_order: bool = False,
                  backward_receive: bool = True, trace: bool = True, fused_receive: bool = False,
                  tiled: Optional[bool] = None, panels: Optional[bool] = None, panel_min_row=B.SPMM_PANEL_MIN_ROW,
-                 panel_piece_cols: int = B.SPMM_PANEL_PIECE_COLS):
+                 panel_piece_cols: int = B.SPMM_PANEL_PIECE_COLS, streams=None):
         self.p = p
         self.device = torch.device(device)
         dev = self.device
@@ -163,8 +163,10 @@ class LayerStep:
                            + B.adaqp_spmm_panels_workspace_bytes(self.panels_dependent.n_per_tile, cfg.dim))
         self.ws_overlap = torch.empty(max(ws_o, 256), dtype=torch.uint8, device=dev)
         self.ws_dependent = torch.empty(max(ws_d, 256), dtype=torch.uint8, device=dev)
-        self.stream_msg = torch.cuda.Stream(device=dev)
-        self.stream_agg = torch.cuda.Stream(device=dev)
+        # streams=(msg, agg): take over an existing pair.  HIP deals streams to a few hardware queues in turn, so a
+        # process that keeps creating streams can end up with a step's two streams on one queue (no overlap)
+        self.stream_msg, self.stream_agg = streams if streams is not None else (torch.cuda.Stream(device=dev),
+                                                                                  torch.cuda.Stream(device=dev))
         self.event_fork = HipEvent()
         self.event_join = HipEvent()
 
