@@ -369,8 +369,9 @@ int adaqp_spmm_panels_workspace_bytes(int32_t n_per_tile, int32_t dim, int64_t *
 
 /* out[r, 0:dim] = sum_j val[j] * H[col[j], 0:dim] (Sec. 2.1 Eq. 3) for the rows r listed in the panels; other
  * rows of out are not touched.  Products and sums in fp32 on the matrix cores (v_mfma_f32_32x32x2_f32); the
- * summation order is fixed by the plan: per piece in panel-column order, then the pieces of a panel in ascending
- * piece number, so runs are bit-identical.  H and out line-padded as for adaqp_spmm_csr_tiled; padding of the
+ * summation order is fixed by the plan: per piece in panel-column order; then the pieces of a panel in four
+ * interleaved runs (every fourth piece of the panel's list, ascending) whose sums are added in run order - so
+ * runs are bit-identical.  H and out line-padded as for adaqp_spmm_csr_tiled; padding of the
  * written rows is set to zero.  A column number outside [0, n_cols) in pcol_dev is clamped into range and a
  * group number outside [0, n_groups] likewise (wrong sums, no stray access); panel rows outside [row_begin,
  * row_end) are skipped.  workspace_dev: 256-byte aligned, >= adaqp_spmm_panels_workspace_bytes.

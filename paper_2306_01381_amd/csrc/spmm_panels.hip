@@ -126,42 +126,55 @@ __global__ __launch_bounds__(kBlock) void spmm_panel_kernel(const PanelArgs a)
     }
 }
 
-// out[row of (panel, m)] = sum of the panel's pieces in ascending piece number; whole lines, row padding zero.
-// One workgroup per panel row, its waves take 256-column strips.
-__global__ __launch_bounds__(kBlock) void spmm_panel_reduce_kernel(const PanelArgs a)
+// out[row of (panel, m)] = sum of the panel's pieces, in a fixed order; whole lines, row padding zero.
+// One workgroup per (panel row, strip of 256 columns).  Its four waves take every fourth piece each (ascending, eight
+// loads in flight) and leave their sums in LDS; wave 0 adds the four in wave order and stores.  A panel has 50-100
+// pieces: one wave walking them all is a chain of a dozen dependent round trips with little else in flight.
+__global__ __launch_bounds__(kBlock) void spmm_panel_reduce_kernel(const PanelArgs a, int32_t n_strips)
 {
+    __shared__ float4_t part[kWavesPerBlock][kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    const int64_t pr = blockIdx.x;                          // panel * 32 + m
+    const int64_t pr = blockIdx.x / (uint32_t)n_strips;     // panel * 32 + m
+    const int32_t strip = (int32_t)(blockIdx.x % (uint32_t)n_strips);
     const int32_t panel = (int32_t)(pr / kPanelRows);
     const int32_t m = (int32_t)(pr % kPanelRows);
     const int64_t row = a.panel_rows[pr];
-    if (row < a.row_begin || row >= a.row_end) return;
+    if (row < a.row_begin || row >= a.row_end) return;      // the whole workgroup: no barrier is skipped by a part
     int32_t s = a.panel_piece_ptr[panel], e = a.panel_piece_ptr[panel + 1];
     s = max(0, min(s, a.n_panel_pieces));
     e = max(s, min(e, a.n_panel_pieces));
     const int32_t n_slots = kTiles * a.n_per_tile;
-    float *o = a.out + row * a.ldo;
-    for (int32_t c = (wave * kWave + lane) * 4; c < a.wdim; c += kBlock * 4) {
-        float4_t sum = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int32_t j = s; j < e; j += 8) {
+    const int32_t c = strip * (kWave * 4) + lane * 4;
+    const bool live = c < a.wdim;
+    float4_t sum = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (live) {
+        for (int32_t j = s + wave; j < e; j += 8 * kWavesPerBlock) {
             float4_t x[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                if (j + q < e) {
-                    const int32_t pid = max(0, min(a.panel_piece[j + q], n_slots - 1));
+                const int32_t jq = j + q * kWavesPerBlock;
+                if (jq < e) {
+                    const int32_t pid = max(0, min(a.panel_piece[jq], n_slots - 1));
                     x[q] = __builtin_nontemporal_load(
                         reinterpret_cast<const float4_t *>(a.ppartial + ((int64_t)pid * kPanelRows + m) * a.wdim + c));
                 }
             }
 #pragma unroll
             for (int q = 0; q < 8; ++q)
-                if (j + q < e) sum += x[q];
+                if (j + q * kWavesPerBlock < e) sum += x[q];
         }
+    }
+    part[wave][lane] = sum;
+    __syncthreads();
+    if (wave == 0 && live) {
+        float4_t total = part[0][lane];
+#pragma unroll
+        for (int w = 1; w < kWavesPerBlock; ++w) total += part[w][lane];
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (c + k >= a.dim) sum[k] = 0.0f;              // row padding
-        __builtin_nontemporal_store(sum, reinterpret_cast<float4_t *>(o + c));
+            if (c + k >= a.dim) total[k] = 0.0f;            // row padding
+        __builtin_nontemporal_store(total, reinterpret_cast<float4_t *>(a.out + row * a.ldo + c));
     }
 }
 
@@ -398,7 +411,10 @@ extern "C" int adaqp_spmm_csr_panels(const adaqp_spmm_panels *p, int64_t row_beg
     // the registers it leaves free let more of that kernel's waves onto the SIMD.
     hipLaunchKernelGGL(spmm_panel_kernel, dim3((unsigned)blocks), dim3(kBlock), (size_t)kPanelIdleLds, st, a);
     ADAQP_HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(spmm_panel_reduce_kernel, dim3((unsigned)(p->n_panels * kPanelRows)), dim3(kBlock), 0, st, a);
+    const int64_t n_strips = (a.wdim + kWave * 4 - 1) / (kWave * 4);
+    const int64_t rblocks = (int64_t)p->n_panels * kPanelRows * n_strips;
+    if (rblocks > 0x7FFFFFFF) return ADAQP_ESIZE;
+    hipLaunchKernelGGL(spmm_panel_reduce_kernel, dim3((unsigned)rblocks), dim3(kBlock), 0, st, a, (int32_t)n_strips);
     ADAQP_HIP_TRY(hipGetLastError());
     return ADAQP_OK;
 }
