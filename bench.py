@@ -443,11 +443,11 @@ def measure_config(name, args, headline, B, torch, np):
         t_p = event_time_ms(st, lambda i: B.adaqp_spmm_csr_panels(pan, rb, re, L.feat, dim, L.out, ws, stream=st), sreps)
         t_t = event_time_ms(st, lambda i: B.adaqp_spmm_csr_tiled(L.rowptr, L.col, L.val, rb, re, L.feat, dim, L.out,
                                                                  off_dev, ws, chunk_cols=chunk, stream=st), sreps)
-        n_chunks = (dim + 127) // 128
+        wdim = (dim + 31) // 32 * 32            # the kernel multiplies whole tiles of 32 feature columns
         panel_parts[tag] = {"panel_rows": int(rows_p.size), "panel_edges": int(deg[rows_p].sum()),
                             "panels": int(pan.c.n_panels), "panel_columns_padded": int(pan.c.n_groups) * 8,
                             "ms_panels": t_p, "ms_tiled_other_rows": t_t,
-                            "mfma_flops_executed": 2.0 * 32 * int(pan.c.n_groups) * 8 * n_chunks * 128}
+                            "mfma_flops_executed": 2.0 * 32 * int(pan.c.n_groups) * 8 * wdim}
         kernels[tag]["panels"] = panel_parts[tag]
     tiled = L.tile_off_overlap is not None or L.tile_off_dependent is not None
     if headline:
@@ -524,7 +524,7 @@ def measure_config(name, args, headline, B, torch, np):
             "executed": {"TFLOPs": executed / t_p / 1e9, "frac": executed / t_p / 1e9 / MFMA_FP32_PEAK_TFLOPS,
                          "panel_density": sum(v["panel_edges"] for v in panel_parts.values())
                          / (32.0 * sum(v["panel_columns_padded"] for v in panel_parts.values())),
-                         "note": "counts the zeros of the dense panels and the padding of dim to 128-column chunks"},
+                         "note": "counts the zeros of the dense panels and the padding of dim to whole tiles of 32 columns"},
             "binding_limit": "the fp32 matrix cores and the gather that feeds them: each neighbour row is fetched once "
                              "per 32-row panel (out of the XCD's L2) and multiplied with the panel's dense "
                              "coefficient table; `frac` counts the method's own multiply-adds (2 * entries * dim)"}

@@ -61,11 +61,76 @@ struct PanelArgs {
     float *ppartial;            // [kTiles * n_per_tile][32][wdim]
 };
 
-// One wave: one piece x one chunk of 128 feature columns.
+// One wave: one piece x one chunk of 128 feature columns (the last chunk of a row may be 32, 64 or 96 wide).
 //
 // v_mfma_f32_32x32x2_f32 computes D[32][32] += A[32][2] * B[2][32] with A's element (m, k) in lane 32k + m,
 // B's element (k, n) in lane 32k + n, and D's element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32) in value
 // v of the lane's 16.  Here m = panel row, k = panel column, n = feature column.
+//
+// T = output tiles of 32 feature columns: lane n of each half-wave takes feature columns T * n .. T * n + T - 1 of
+// one row of H, value t of those is the B operand of tile t.  T = 4 everywhere but in a narrower last chunk, which
+// then costs T / 4 of the matrix instructions instead of multiplying padding.
+template <int T>
+__device__ __forceinline__ void panel_piece(const PanelArgs &a, int64_t pid, int32_t g0, int32_t g1, uint32_t chunk,
+                                            int lane)
+{
+    const int half = lane >> 5, n = lane & 31;
+    const int32_t c0 = (int32_t)chunk * kChunk + T * n;     // < wdim: the chunk is 32 * T columns wide
+    const float *hbase = a.H + c0;
+    const uint32_t last_col = (uint32_t)a.n_cols - 1u;
+
+    float16_t acc[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+
+    auto meta = [&](int32_t g, int4_t *cols, float4_t *al) {
+        *cols = *reinterpret_cast<const int4_t *>(a.pcol + ((int64_t)g * 2 + half) * 4);
+        *al = *reinterpret_cast<const float4_t *>(a.palpha + ((int64_t)g * kWave + lane) * 4);
+    };
+    int4_t cols, ncols;
+    float4_t al, nal;
+    meta(g0, &cols, &al);
+    ncols = cols;
+    nal = al;
+    for (int32_t g = g0; g < g1; ++g) {
+        float x[4][T];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t c = min((uint32_t)cols[u], last_col);            // a corrupt plan cannot lead outside H
+            const float *src = hbase + (int64_t)c * a.ldh;
+            if (T == 4) {
+                const float4_t v4 = *reinterpret_cast<const float4_t *>(src);
+#pragma unroll
+                for (int t = 0; t < T; ++t) x[u][t] = v4[t];
+            } else {
+#pragma unroll
+                for (int t = 0; t < T; ++t) x[u][t] = src[t];
+            }
+        }
+        if (g + 1 < g1) meta(g + 1, &ncols, &nal);                          // in flight during the MFMAs
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int t = 0; t < T; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(al[u], x[u][t], acc[t], 0, 0, 0);
+        cols = ncols;
+        al = nal;
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int m = 8 * (v / 4) + 4 * half + (v % 4);
+        float *dst = a.ppartial + (pid * kPanelRows + m) * a.wdim + c0;
+        if (T == 4) {
+            float4_t r = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+            __builtin_nontemporal_store(r, reinterpret_cast<float4_t *>(dst));
+        } else {
+#pragma unroll
+            for (int t = 0; t < T; ++t) __builtin_nontemporal_store(acc[t][v], dst + t);
+        }
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void spmm_panel_kernel(const PanelArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -81,49 +146,12 @@ __global__ __launch_bounds__(kBlock) void spmm_panel_kernel(const PanelArgs a)
     g0 = max(0, min(g0, a.n_groups));
     g1 = min(g1, a.n_groups);
     if (g0 >= g1) return;
-    const int half = lane >> 5, n = lane & 31;
-    const int32_t c0 = (int32_t)chunk * kChunk + 4 * n;
-    const bool live = c0 < a.wdim;
-    const float *hbase = a.H + (live ? c0 : 0);
-    const uint32_t last_col = (uint32_t)a.n_cols - 1u;
-
-    float16_t acc[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
-
-    auto meta = [&](int32_t g, int4_t *cols, float4_t *al) {
-        *cols = *reinterpret_cast<const int4_t *>(a.pcol + ((int64_t)g * 2 + half) * 4);
-        *al = *reinterpret_cast<const float4_t *>(a.palpha + ((int64_t)g * kWave + lane) * 4);
-    };
-    int4_t cols, ncols;
-    float4_t al, nal;
-    meta(g0, &cols, &al);
-    ncols = cols;
-    nal = al;
-    for (int32_t g = g0; g < g1; ++g) {
-        float4_t x[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint32_t c = min((uint32_t)cols[u], last_col);            // a corrupt plan cannot lead outside H
-            x[u] = *reinterpret_cast<const float4_t *>(hbase + (int64_t)c * a.ldh);
-        }
-        if (g + 1 < g1) meta(g + 1, &ncols, &nal);                          // in flight during the MFMAs
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(al[u], x[u][t], acc[t], 0, 0, 0);
-        cols = ncols;
-        al = nal;
-    }
-    if (!live) return;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int m = 8 * (v / 4) + 4 * half + (v % 4);
-        float4_t r = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
-        __builtin_nontemporal_store(r, reinterpret_cast<float4_t *>(a.ppartial + (pid * kPanelRows + m) * a.wdim + c0));
-    }
+    // width of this chunk in tiles of 32 columns (wdim is a multiple of 32): 4 but possibly for the last chunk
+    const int32_t left = a.wdim - (int32_t)chunk * kChunk;
+    if (left >= kChunk) panel_piece<4>(a, pid, g0, g1, chunk, lane);
+    else if (left == 96) panel_piece<3>(a, pid, g0, g1, chunk, lane);
+    else if (left == 64) panel_piece<2>(a, pid, g0, g1, chunk, lane);
+    else if (left == 32) panel_piece<1>(a, pid, g0, g1, chunk, lane);
 }
 
 // out[row of (panel, m)] = sum of the panel's pieces, in a fixed order; whole lines, row padding zero.
